@@ -1,0 +1,199 @@
+#!/usr/bin/env python3
+"""Throughput of the DEF / DEF-A compression-and-update step on one MI355X.
+
+One "step" is one pass of the whole hot path (block draw, fused momentum +
+error-feedback + residual pass over all W workers, cross-worker average of the
+kept block, parameter update) over one set of synthetic per-worker gradients
+that is already resident in HBM.
+
+Default workload: the ResNet-50-shaped configuration (d = 25,557,032 parameters
+in 161 tensors, W = 16 workers, ratio 1/128, momentum 0.9, weight decay 1e-4).
+
+Prints ONE JSON line.  `value` is the algorithmic HBM traffic of a step divided
+by the measured time per step; `roofline` prices the streaming kernel alone
+(measured with HIP events around each of its launches, on the stream it runs on)
+against the 8 TB/s HBM peak; `cpu_baseline` times the plain C oracle on this
+host's cores on a bounded number of steps of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0   # MI355X HBM3E peak, GB/s
+
+# HBM bytes per launch of the streaming kernel from rocprofv3 FETCH_SIZE + WRITE_SIZE,
+# each scaled by what the same counter reads for a 1 GiB copy
+# (profiles/def_stream_vec4_kernel_resnet50_shaped_hbm_counters.md).  Keyed by workload
+# and by the exact kernel instantiation, so a changed kernel reports null until the
+# counters are taken again.
+MEASURED_TRAFFIC = {
+    ("resnet50_shaped",
+     "def_stream_vec4_kernel<mu=1,wd=1,threads=64,quads=1,nt=1,order=blocked:16384>"): 8306161344,
+}
+
+
+def algorithmic_bytes(w, y_out=False):
+    """Bytes the method itself must move per step (fp32): per (worker, index) one
+    gradient read, error memory read+write and, with momentum, momentum read+write;
+    plus x: read once everywhere when weight decay needs it, else read on the
+    block; written on the block.  The compact staging of the kept block between
+    the two kernels is not counted."""
+    per_elem = 12 + (8 if w.momentum != 0 else 0)
+    stream = w.W * w.d * per_elem
+    if w.weight_decay != 0:
+        stream_x, block = 4 * w.d, 4 * w.B
+    else:
+        stream_x, block = 0, 8 * w.B
+    extra = 0
+    if y_out:
+        extra = 4 * w.d + (0 if w.weight_decay != 0 else 4 * w.d)
+    return dict(step=stream + stream_x + block + extra, stream_kernel=stream + stream_x)
+
+
+def cpu_baseline(w, ld, budget_s=15.0):
+    """Time the plain C oracle (oracle/def_oracle.c, as it stands) on this host:
+    full d and W of the workload, as many steps as fit the budget."""
+    import numpy as np
+    from oracle.c_oracle import DefOracleC
+    from paper_2004_05298_amd import workloads as wl
+
+    x0 = wl.initial_params(w)
+    g = wl.gradient_set(w, 0, ld=w.d, threads=16)
+    ora = DefOracleC(x0, w.W, w.R, w.lr, w.momentum, w.weight_decay, w.seed)
+    ora.step(g)                     # first touch of the state pages, not timed
+    steps, t0 = 0, time.perf_counter()
+    while True:
+        ora.step(g)
+        steps += 1
+        dt = time.perf_counter() - t0
+        if dt >= budget_s or steps >= w.T:
+            break
+    per_step = dt / steps
+    ab = algorithmic_bytes(w)["step"]
+    return {
+        "value": ab / per_step / 1e9, "unit": "GB/s", "cores": ora.threads, "kind": "oracle",
+        "steps_per_s": 1.0 / per_step,
+        "sample": f"{steps} full steps of {w.name} (d={w.d}, W={w.W}) by the plain C oracle "
+                  f"with {ora.threads} OpenMP threads, after one untimed step",
+    }
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="resnet50_shaped")
+    ap.add_argument("--variant", default=None, choices=[None, "def", "def_a"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-budget", type=float, default=15.0)
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="N",
+                    help="first run N plain device-to-device copies of a 1 GiB tensor (a kernel of "
+                         "known traffic, 2^30 bytes read and 2^30 written per launch, against which "
+                         "hardware counters are scaled); not part of the timed region")
+    args = ap.parse_args()
+
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: the library runs all W workers' shares on ONE GPU; there is no "
+              "multi-GPU path, run with --gpus 1", file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2004_05298_amd import binding, workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    if not os.path.exists(binding._build.library_path()):
+        binding._build.build_library()
+    binding.load_library()
+    torch.cuda.set_device(0)
+
+    if args.copy_calibration:
+        src = torch.zeros(1 << 28, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(args.copy_calibration):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
+    w = wl.by_name(args.workload)
+    variant = args.variant or ("def_a" if w.variant == "def_a" else "def")
+    ld = wl.padded_ld(w.d)
+    x = torch.from_numpy(wl.initial_params(w)).cuda()
+    pool = wl.device_gradient_pool(w, ld)
+    stream = torch.cuda.current_stream().cuda_stream
+    ctx = binding.DefContext(w.d, w.W, w.R, w.lr, w.momentum, w.weight_decay, w.seed, params=x,
+                             tensor_offsets=w.tensor_offsets(), stream=stream)
+
+    def one_step(t):
+        forced = w.forced_start(t)
+        if forced is not None:
+            ctx.force_next_start(forced)
+        if variant == "def_a":
+            ctx.a_step(pool[t % w.pool], ld)
+        else:
+            ctx.step(pool[t % w.pool], ld, None)
+
+    t = 0
+    for _ in range(args.warmup):
+        one_step(t)
+        t += 1
+    torch.cuda.synchronize()
+    ctx.profile_begin(args.steps)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        one_step(t)
+        t += 1
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    kernel_ms = ctx.profile_end(args.steps)
+    vectorised = ctx.last_path_vectorised()
+    kernel_name = ctx.last_kernel()
+    ctx.destroy()
+
+    ab = algorithmic_bytes(w)
+    per_step = elapsed / args.steps
+    value = ab["step"] / per_step / 1e9
+    k_avg_ms = sum(kernel_ms) / len(kernel_ms)
+    achieved = ab["stream_kernel"] / (k_avg_ms * 1e-3) / 1e9
+    out = {
+        "metric": "DEF step throughput: achieved HBM GB/s (% of peak) and steps/s at d, W",
+        "value": round(value, 2), "unit": "GB/s",
+        "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBS, 2),
+        "steps_per_s": round(1.0 / per_step, 2),
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(per_step * 1e3, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": w.name, "d": w.d, "W": w.W, "R": w.R, "B": w.B,
+                   "n_tensors": w.n_tensors, "momentum": w.momentum,
+                   "weight_decay": w.weight_decay, "lr": w.lr, "variant": variant,
+                   "gradient_sets": w.pool, "path": "dwordx4" if vectorised else "dword",
+                   "algorithmic_bytes_per_step": ab["step"]},
+        "roofline": {"bound": "hbm", "kernel": kernel_name,
+                     "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBS, 4),
+                     "avg_launch_ms": round(k_avg_ms, 5), "launches": len(kernel_ms),
+                     "algorithmic_bytes_per_launch": ab["stream_kernel"],
+                     "traffic": MEASURED_TRAFFIC.get((w.name, kernel_name))},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, ld, args.cpu_budget)
+        for k in ("value", "steps_per_s"):
+            out["cpu_baseline"][k] = round(out["cpu_baseline"][k], 3)
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

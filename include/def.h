@@ -1,0 +1,202 @@
+/*
+ * def.h -- C ABI of the DEF / DEF-A compression-and-update step with random
+ * block-wise gradient sparsification (RBGS) for one AMD MI355X (gfx950).
+ *
+ * Method: Xu & Huang, "Detached Error Feedback for Distributed SGD with Random
+ * Sparsification" (arXiv 2004.05298).  One call of def_step / def_a_step is one
+ * iteration t of Algorithm 1 for all W (the paper's K) data-parallel workers,
+ * whose gradients, error memories and momentum buffers all live on this GPU:
+ *
+ *   m_k <- mu*m_k + g_k                       Sec. 3.2 "Momentum Variant"
+ *   p_k  = eta*m_k + e_k                      Algorithm 1, error-feedback line
+ *   e_k <- p_k - C(p_k)                       Algorithm 1, residual line
+ *   C(p) = (1/W) sum_k C(p_k)                 Algorithm 1, ring-allreduce line
+ *   x   <- x - C(p)                           Algorithm 1, update line
+ *
+ * C is RBGS (Sec. 1): it keeps one contiguous block of the flattened vector and
+ * zeroes the rest; every worker draws the same block from a shared seed.
+ *
+ * Conventions
+ *   - All floating-point buffers are IEEE binary32; every multiply and add is
+ *     rounded separately (no fused multiply-add), so results do not depend on
+ *     the launch shape.
+ *   - "DEVICE" pointers are HIP device memory on the GPU that was current when
+ *     def_init was called; "HOST" pointers are ordinary process memory.
+ *   - Every function returns DEF_OK (0) or a negative def_status.  No function
+ *     throws or aborts.  A call that returns DEF_EINVAL has changed nothing.
+ *   - def_step / def_a_step / def_output only enqueue work on the context's
+ *     stream and return; they never synchronise with the device.
+ *   - A context is not thread-safe; use one context per host thread.
+ */
+#ifndef DEF_H_
+#define DEF_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum def_status {
+    DEF_OK = 0,
+    DEF_EINVAL = -1,   /* bad argument: NULL pointer, bad shape, bad offset table, ld < d, ... */
+    DEF_ENOMEM = -2,   /* device or host allocation failed                                      */
+    DEF_EHIP = -3      /* a HIP runtime call failed; def_last_hip_error() has its code          */
+} def_status;
+
+typedef struct def_ctx def_ctx; /* opaque, owned by the library */
+
+/*
+ * Problem statement (Algorithm 1 "Input"; Sec. 3.2 for mu; Sec. 1 for the seed).
+ */
+typedef struct def_config {
+    uint64_t d;             /* number of parameters, 1 <= d < 2^40                              */
+    uint32_t W;             /* number of workers (the paper's K), >= 1                          */
+    uint32_t R;             /* compression ratio, integer, 1 <= R <= d.  The kept block has
+                               B = ceil(d/R) elements (delta = B/d, Assumption 5).              */
+    float lr;               /* learning rate eta                                                */
+    float momentum;         /* mu.  0 selects Algorithm 1 as printed: p = eta*g + e, and no
+                               momentum buffer is allocated.                                    */
+    float weight_decay;     /* wd.  0 = off.  Otherwise g' = g + wd*x_t replaces g (decay folded
+                               into the gradient at the shared iterate, before momentum).       */
+    uint64_t seed;          /* shared random seed of the block draw                             */
+    const uint64_t *tensor_offsets; /* HOST, n_tensors+1 entries: off[0]=0 < off[1] < ... <
+                               off[n_tensors]=d.  Tensor l of the model occupies flat indices
+                               [off[l], off[l+1]).  NULL means one tensor of length d.  Copied. */
+    uint32_t n_tensors;     /* L >= 1 (ignored when tensor_offsets is NULL)                     */
+    float *params;          /* DEVICE, d floats: the model x as ONE flat vector, caller-owned,
+                               updated in place.  NULL selects tensor mode (param_ptrs).        */
+    float *const *param_ptrs; /* HOST array of n_tensors DEVICE pointers; tensor l has
+                               off[l+1]-off[l] floats, caller-owned, updated in place.  Used
+                               only when params == NULL.  The array is copied.                  */
+    void *stream;           /* hipStream_t all work is enqueued on (NULL = the null stream)     */
+} def_config;
+
+/*
+ * Create a context: validates cfg, allocates and zero-fills the W error
+ * memories (e_{k,0}=0, Algorithm 1 "Initialize"), the W momentum buffers
+ * (m_{k,0}=0, Sec. 3.2) unless momentum == 0, the compact message buffer
+ * [W][B] and the averaged block [B].  Step counter t starts at 0.
+ * *out is written only on success.  Synchronises the stream once.
+ */
+int def_init(def_ctx **out, const def_config *cfg);
+
+/* Frees everything def_init allocated (synchronises the stream first). */
+int def_destroy(def_ctx *ctx);
+
+/*
+ * One DEF iteration (Algorithm 1, inner loop, with the momentum variant).
+ *   grads  DEVICE, read-only: worker k's flat gradient g_{k,t} starts at
+ *          grads + k*ld; ld >= d elements.  Tensor l sits at +off[l].  Must stay
+ *          valid until the stream has executed the step.  If grads is 16-byte
+ *          aligned and ld is a multiple of 4 the vectorised path runs; any other
+ *          alignment is accepted and takes the element-wise path.
+ *   y_out  DEVICE or NULL.  If not NULL, d floats receive DEF's output
+ *          y_{t+1} = x_{t+1} - (1/W) sum_k e_{k,t+1}   (Algorithm 1 "Output";
+ *          Sec. 3.2, Eq. "y update").  The paper needs y only when the model is
+ *          evaluated, so pass NULL in the training loop.
+ * Draws s_t = def_block_start(seed, t, d) (or the forced start), keeps the
+ * circular block {(s_t + j) mod d : 0 <= j < B}, then t <- t+1.
+ */
+int def_step(def_ctx *ctx, const float *grads, uint64_t ld, float *y_out);
+
+/*
+ * One DEF-A iteration.  DEF-A runs the same iteration as DEF and returns x_T
+ * instead of y_T (Algorithm 1 "Output"; Sec. 3.2 "DEF-A"), so this is def_step
+ * with no y: after it, params holds DEF-A's model.
+ */
+int def_a_step(def_ctx *ctx, const float *grads, uint64_t ld);
+
+/*
+ * Tensor mode of the two steps: gradients are given per tensor.
+ *   grad_ptrs  HOST array of W*n_tensors DEVICE pointers; entry k*n_tensors + l
+ *              is worker k's gradient of tensor l (off[l+1]-off[l] floats, any
+ *              4-byte alignment).  The table is copied to the device when it
+ *              differs from the one used by the previous call; that copy
+ *              synchronises the stream, an unchanged table costs nothing.
+ *   y_out      as in def_step (one flat vector of d floats) or NULL.
+ * Works with either parameter mode.
+ */
+int def_step_tensors(def_ctx *ctx, const float *const *grad_ptrs, float *y_out);
+int def_a_step_tensors(def_ctx *ctx, const float *const *grad_ptrs);
+
+/*
+ * DEF's output without stepping: y_out[i] = x[i] - (1/W) sum_k e_k[i] for the
+ * current state (Algorithm 1 "Output").  y_out: DEVICE, d floats.
+ */
+int def_output(def_ctx *ctx, float *y_out);
+
+/* Replace the seed (Sec. 1: the seed all workers share).  t keeps counting. */
+int def_set_seed(def_ctx *ctx, uint64_t seed);
+
+/* Learning-rate schedules (eta_t in Theorem 1; step decay in Sec. 5 "Settings"). */
+int def_set_lr(def_ctx *ctx, float lr);
+
+/* Step counter, for resuming: the state of a run is (x, e, m, seed, t, eta). */
+int def_set_step(def_ctx *ctx, uint64_t t);
+int def_get_step(const def_ctx *ctx, uint64_t *t);
+
+/*
+ * Use start index s (0 <= s < d) for the NEXT step only instead of the seeded
+ * draw; s < 0 clears a pending request.  For tests and for workloads that force
+ * a block across the end of the vector.
+ */
+int def_force_next_start(def_ctx *ctx, int64_t s);
+
+/* Start index and length B of the block kept by the most recent step. */
+int def_last_block(const def_ctx *ctx, uint64_t *start, uint64_t *len);
+
+/*
+ * The shared block draw as a pure function (HOST, no GPU needed):
+ *   *start = Philox4x64-10(counter = (t,0,0,0), key = (seed,0))[0] mod d.
+ * (Salmon et al., "Parallel random numbers: as easy as 1, 2, 3", SC 2011.)
+ */
+int def_block_start(uint64_t seed, uint64_t t, uint64_t d, uint64_t *start);
+
+/*
+ * DEVICE views of the library-owned state, for checkpoints and parity checks.
+ *   *e, *m       [W][*ld_state] floats, worker k's row at + k * *ld_state, column i
+ *                = flat parameter index i; *ld_state >= d (a multiple of 64);
+ *                columns d..ld_state-1 are padding and stay zero.
+ *                *m is NULL when momentum == 0.
+ *   *avg_block   B floats: the averaged block C(p_t) of the last step in compact
+ *                form, entry j belongs to flat index (start + j) mod d.
+ * Any out-pointer may be NULL.  The views stay valid until def_destroy; writing
+ * through e/m (restoring a checkpoint) is allowed between steps.
+ */
+int def_state_ptrs(def_ctx *ctx, float **e, float **m, float **avg_block, uint64_t *ld_state);
+
+/* Which path the last step took: 1 = vectorised flat path, 0 = element-wise path. */
+int def_last_path(const def_ctx *ctx, int *vectorised);
+
+/*
+ * Name and launch shape of the streaming kernel the last step ran, e.g.
+ * "def_stream_vec4_kernel<mu=1,wd=1,threads=64,quads=1,nt=1,order=blocked:16384>".
+ * For profiles and benchmarks that must say exactly which kernel they measured.
+ * The string is owned by the context and valid until the next step or def_destroy;
+ * NULL if no step has run.
+ */
+const char *def_last_kernel(const def_ctx *ctx);
+
+/*
+ * Per-launch timing of the streaming kernel (the fused momentum + error
+ * feedback + residual pass, which moves nearly all of a step's bytes), with HIP
+ * events recorded on the context's stream immediately before and after that
+ * launch.
+ *   def_profile_begin  allocates max_steps event pairs; the next max_steps steps
+ *                      each record one pair (later steps are not recorded).
+ *   def_profile_end    waits for the last recorded event, writes up to cap
+ *                      durations in milliseconds to ms (HOST), stores the
+ *                      number recorded in *n, and frees the events.
+ */
+int def_profile_begin(def_ctx *ctx, uint32_t max_steps);
+int def_profile_end(def_ctx *ctx, float *ms, uint32_t cap, uint32_t *n);
+
+/* Text for a def_status; HIP error code of the last DEF_EHIP (0 if none). */
+const char *def_strerror(int status);
+int def_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DEF_H_ */

@@ -1,0 +1,422 @@
+// Host side of the DEF / DEF-A step library: the C ABI declared in include/def.h.
+// Validation, the shared block draw, state allocation and kernel sequencing.
+// No arithmetic of the method happens on the host except the O(1) block draw
+// (arXiv 2004.05298, Sec. 1: one uniformly sampled start index per iteration).
+#include "def.h"
+#include "def_internal.h"
+
+#include <cstring>
+#include <new>
+#include <vector>
+
+namespace {
+
+thread_local int g_last_hip_error = 0;
+
+int hip_fail(hipError_t err)
+{
+    g_last_hip_error = (int)err;
+    (void)hipGetLastError();   // clear the sticky error so that later calls start clean
+    return err == hipErrorOutOfMemory ? DEF_ENOMEM : DEF_EHIP;
+}
+
+#define DEF_HIP(call)                                   \
+    do {                                                \
+        hipError_t err__ = (call);                      \
+        if (err__ != hipSuccess) return hip_fail(err__); \
+    } while (0)
+
+// Philox4x64-10 (Salmon, Moraes, Dror, Shaw, SC 2011): ten rounds of two
+// 64x64->128-bit multiplications whose halves are crossed with the other counter
+// words and the key; the key advances by the Weyl constants between rounds.
+void philox4x64_10(uint64_t ctr[4], const uint64_t key_in[2])
+{
+    const uint64_t mul0 = 0xD2E7470EE14C6C93ull, mul1 = 0xCA5A826395121157ull;
+    const uint64_t weyl0 = 0x9E3779B97F4A7C15ull, weyl1 = 0xBB67AE8584CAA73Bull;
+    uint64_t k0 = key_in[0], k1 = key_in[1];
+    for (int round = 0; round < 10; ++round) {
+        const unsigned __int128 p0 = (unsigned __int128)mul0 * ctr[0];
+        const unsigned __int128 p1 = (unsigned __int128)mul1 * ctr[2];
+        const uint64_t n0 = (uint64_t)(p1 >> 64) ^ ctr[1] ^ k0;
+        const uint64_t n1 = (uint64_t)p1;
+        const uint64_t n2 = (uint64_t)(p0 >> 64) ^ ctr[3] ^ k1;
+        const uint64_t n3 = (uint64_t)p0;
+        ctr[0] = n0; ctr[1] = n1; ctr[2] = n2; ctr[3] = n3;
+        k0 += weyl0;
+        k1 += weyl1;
+    }
+}
+
+uint64_t draw_start(uint64_t seed, uint64_t t, uint64_t d)
+{
+    uint64_t ctr[4] = {t, 0, 0, 0};
+    const uint64_t key[2] = {seed, 0};
+    philox4x64_10(ctr, key);
+    return ctr[0] % d;
+}
+
+uint64_t round_up(uint64_t v, uint64_t to) { return (v + to - 1) / to * to; }
+
+}  // namespace
+
+struct def_ctx {
+    // problem
+    uint64_t d = 0, B = 0, seed = 0, t = 0;
+    uint32_t W = 0, R = 0, L = 0;
+    float lr = 0, mu = 0, wd = 0;
+    int64_t forced = -1;
+    uint64_t last_start = 0;
+    bool has_last = false;
+    int last_vec = 0;
+    hipStream_t stream = nullptr;
+    // device state owned by the library
+    float *e = nullptr, *m = nullptr, *msg = nullptr, *avg = nullptr;
+    uint64_t ld = 0, ldmsg = 0;
+    uint64_t *d_off = nullptr;
+    DefChunk *d_chunks = nullptr;
+    uint32_t n_chunks = 0;
+    // parameters
+    float *x_flat = nullptr;
+    float **d_xptrs = nullptr;
+    // gradient pointer table (tensor mode)
+    const float **d_gptrs = nullptr;
+    std::vector<const float *> h_gptrs;
+    // per-launch timing of the streaming kernel
+    std::vector<hipEvent_t> ev;
+    uint32_t prof_cap = 0, prof_n = 0;
+    char kernel_name[160] = {0};
+};
+
+namespace {
+
+void free_ctx(def_ctx *c)
+{
+    if (!c) return;
+    for (hipEvent_t ev : c->ev) (void)hipEventDestroy(ev);
+    (void)hipFree(c->e);
+    (void)hipFree(c->m);
+    (void)hipFree(c->msg);
+    (void)hipFree(c->avg);
+    (void)hipFree(c->d_off);
+    (void)hipFree(c->d_chunks);
+    (void)hipFree(c->d_xptrs);
+    (void)hipFree(c->d_gptrs);
+    delete c;
+}
+
+DefStepArgs base_args(const def_ctx *c, uint64_t s)
+{
+    DefStepArgs a{};
+    a.d = c->d; a.B = c->B; a.s = s; a.W = c->W;
+    a.lr = c->lr; a.mu = c->mu; a.wd = c->wd;
+    a.e = c->e; a.m = c->m; a.ld = c->ld;
+    a.msg = c->msg; a.ldmsg = c->ldmsg; a.avg = c->avg;
+    a.x_flat = c->x_flat; a.x_ptrs = c->d_xptrs; a.off = c->d_off; a.L = c->L;
+    a.chunks = c->d_chunks; a.n_chunks = c->n_chunks;
+    return a;
+}
+
+// The sequence of one iteration: streaming pass, average + update, optional y.
+int run_step(def_ctx *c, DefStepArgs &a, bool vec, float *y_out)
+{
+    const bool prof = c->prof_n < c->prof_cap;
+    if (prof) DEF_HIP(hipEventRecord(c->ev[2 * c->prof_n], c->stream));
+    DEF_HIP(vec ? def_launch_stream_vec4(a, c->stream) : def_launch_stream_elem(a, c->stream));
+    if (prof) {
+        DEF_HIP(hipEventRecord(c->ev[2 * c->prof_n + 1], c->stream));
+        ++c->prof_n;
+    }
+    DEF_HIP(def_launch_average_update(a, c->stream));
+    if (y_out) DEF_HIP(def_launch_output(a, y_out, c->stream));
+    c->last_start = a.s;
+    c->has_last = true;
+    c->last_vec = vec ? 1 : 0;
+    def_describe_stream_kernel(a, vec, c->kernel_name, sizeof c->kernel_name);
+    c->forced = -1;
+    ++c->t;
+    return DEF_OK;
+}
+
+uint64_t next_start(const def_ctx *c)
+{
+    return c->forced >= 0 ? (uint64_t)c->forced : draw_start(c->seed, c->t, c->d);
+}
+
+}  // namespace
+
+extern "C" {
+
+int def_block_start(uint64_t seed, uint64_t t, uint64_t d, uint64_t *start)
+{
+    if (!start || d == 0) return DEF_EINVAL;
+    *start = draw_start(seed, t, d);
+    return DEF_OK;
+}
+
+int def_init(def_ctx **out, const def_config *cfg)
+{
+    if (!out || !cfg) return DEF_EINVAL;
+    if (cfg->d == 0 || cfg->d >= (1ull << 40) || cfg->W == 0 || cfg->R == 0 || cfg->R > cfg->d)
+        return DEF_EINVAL;
+    if (!(cfg->lr == cfg->lr) || !(cfg->momentum == cfg->momentum) ||
+        !(cfg->weight_decay == cfg->weight_decay))
+        return DEF_EINVAL;   // NaN hyper-parameters
+    const uint32_t L = cfg->tensor_offsets ? cfg->n_tensors : 1;
+    if (L == 0) return DEF_EINVAL;
+    if (cfg->tensor_offsets) {
+        if (cfg->tensor_offsets[0] != 0 || cfg->tensor_offsets[L] != cfg->d) return DEF_EINVAL;
+        for (uint32_t l = 0; l < L; ++l)
+            if (cfg->tensor_offsets[l] >= cfg->tensor_offsets[l + 1]) return DEF_EINVAL;
+    }
+    if (!cfg->params) {
+        if (!cfg->param_ptrs) return DEF_EINVAL;
+        for (uint32_t l = 0; l < L; ++l)
+            if (!cfg->param_ptrs[l] || (uintptr_t)cfg->param_ptrs[l] % 4 != 0) return DEF_EINVAL;
+    } else if ((uintptr_t)cfg->params % 4 != 0) {
+        return DEF_EINVAL;
+    }
+
+    def_ctx *c = new (std::nothrow) def_ctx;
+    if (!c) return DEF_ENOMEM;
+    c->d = cfg->d; c->W = cfg->W; c->R = cfg->R; c->L = L;
+    c->B = (cfg->d + cfg->R - 1) / cfg->R;                       // B = ceil(d/R)
+    c->lr = cfg->lr; c->mu = cfg->momentum; c->wd = cfg->weight_decay;
+    c->seed = cfg->seed;
+    c->stream = (hipStream_t)cfg->stream;
+    c->x_flat = cfg->params;
+    c->ld = round_up(c->d, 64);
+    c->ldmsg = round_up(c->B, DEF_AVG_TILE);
+
+    // host tables: offsets and the work list of the element-wise kernel
+    std::vector<uint64_t> off(L + 1);
+    std::vector<DefChunk> chunks;
+    try {
+        if (cfg->tensor_offsets) off.assign(cfg->tensor_offsets, cfg->tensor_offsets + L + 1);
+        else { off[0] = 0; off[1] = c->d; }
+        for (uint32_t l = 0; l < L; ++l)
+            for (uint64_t a = off[l]; a < off[l + 1]; a += DEF_ELEM_CHUNK) {
+                const uint64_t len = off[l + 1] - a < DEF_ELEM_CHUNK ? off[l + 1] - a : DEF_ELEM_CHUNK;
+                chunks.push_back(DefChunk{a, (uint32_t)len, l});
+            }
+        c->h_gptrs.reserve((size_t)c->W * L);
+    } catch (const std::bad_alloc &) {
+        free_ctx(c);
+        return DEF_ENOMEM;
+    }
+    if (chunks.size() > 0x7fffffffull) { free_ctx(c); return DEF_EINVAL; }
+    c->n_chunks = (uint32_t)chunks.size();
+
+#define DEF_INIT_HIP(call)                                                      \
+    do {                                                                        \
+        hipError_t err__ = (call);                                              \
+        if (err__ != hipSuccess) { free_ctx(c); return hip_fail(err__); }       \
+    } while (0)
+
+    const size_t state_bytes = (size_t)c->W * c->ld * sizeof(float);
+    const size_t msg_bytes = (size_t)c->W * c->ldmsg * sizeof(float);
+    DEF_INIT_HIP(hipMalloc((void **)&c->e, state_bytes));
+    if (c->mu != 0.0f) DEF_INIT_HIP(hipMalloc((void **)&c->m, state_bytes));
+    DEF_INIT_HIP(hipMalloc((void **)&c->msg, msg_bytes));
+    DEF_INIT_HIP(hipMalloc((void **)&c->avg, c->ldmsg * sizeof(float)));
+    DEF_INIT_HIP(hipMalloc((void **)&c->d_off, (L + 1) * sizeof(uint64_t)));
+    DEF_INIT_HIP(hipMalloc((void **)&c->d_chunks, chunks.size() * sizeof(DefChunk)));
+    DEF_INIT_HIP(hipMemsetAsync(c->e, 0, state_bytes, c->stream));           // e_{k,0} = 0
+    if (c->m) DEF_INIT_HIP(hipMemsetAsync(c->m, 0, state_bytes, c->stream)); // m_{k,0} = 0
+    DEF_INIT_HIP(hipMemsetAsync(c->msg, 0, msg_bytes, c->stream));
+    DEF_INIT_HIP(hipMemsetAsync(c->avg, 0, c->ldmsg * sizeof(float), c->stream));
+    DEF_INIT_HIP(hipMemcpyAsync(c->d_off, off.data(), (L + 1) * sizeof(uint64_t),
+                                hipMemcpyHostToDevice, c->stream));
+    DEF_INIT_HIP(hipMemcpyAsync(c->d_chunks, chunks.data(), chunks.size() * sizeof(DefChunk),
+                                hipMemcpyHostToDevice, c->stream));
+    if (!c->x_flat) {
+        DEF_INIT_HIP(hipMalloc((void **)&c->d_xptrs, L * sizeof(float *)));
+        DEF_INIT_HIP(hipMemcpyAsync(c->d_xptrs, cfg->param_ptrs, L * sizeof(float *),
+                                    hipMemcpyHostToDevice, c->stream));
+    }
+    DEF_INIT_HIP(hipStreamSynchronize(c->stream));   // host tables go out of scope below
+#undef DEF_INIT_HIP
+    *out = c;
+    return DEF_OK;
+}
+
+int def_destroy(def_ctx *ctx)
+{
+    if (!ctx) return DEF_EINVAL;
+    const hipError_t err = hipStreamSynchronize(ctx->stream);
+    free_ctx(ctx);
+    return err == hipSuccess ? DEF_OK : hip_fail(err);
+}
+
+int def_step(def_ctx *ctx, const float *grads, uint64_t ld, float *y_out)
+{
+    if (!ctx || !grads || ld < ctx->d || (uintptr_t)grads % 4 != 0) return DEF_EINVAL;
+    if (y_out && (uintptr_t)y_out % 4 != 0) return DEF_EINVAL;
+    DefStepArgs a = base_args(ctx, next_start(ctx));
+    a.g_flat = grads;
+    a.ldg = ld;
+    a.g_ptrs = nullptr;
+    // x is read by the streaming pass only for weight decay
+    const bool x_ok = ctx->wd == 0.0f || (ctx->x_flat && (uintptr_t)ctx->x_flat % 16 == 0);
+    const bool vec = (uintptr_t)grads % 16 == 0 && ld % 4 == 0 && x_ok;
+    return run_step(ctx, a, vec, y_out);
+}
+
+int def_a_step(def_ctx *ctx, const float *grads, uint64_t ld)
+{
+    return def_step(ctx, grads, ld, nullptr);
+}
+
+int def_step_tensors(def_ctx *ctx, const float *const *grad_ptrs, float *y_out)
+{
+    if (!ctx || !grad_ptrs) return DEF_EINVAL;
+    if (y_out && (uintptr_t)y_out % 4 != 0) return DEF_EINVAL;
+    const size_t n = (size_t)ctx->W * ctx->L;
+    for (size_t q = 0; q < n; ++q)
+        if (!grad_ptrs[q] || (uintptr_t)grad_ptrs[q] % 4 != 0) return DEF_EINVAL;
+    const bool same = ctx->d_gptrs && ctx->h_gptrs.size() == n &&
+                      std::memcmp(ctx->h_gptrs.data(), grad_ptrs, n * sizeof(float *)) == 0;
+    if (!same) {
+        if (!ctx->d_gptrs) DEF_HIP(hipMalloc((void **)&ctx->d_gptrs, n * sizeof(float *)));
+        // the previous table may still be in use by a step in flight
+        DEF_HIP(hipStreamSynchronize(ctx->stream));
+        DEF_HIP(hipMemcpy(ctx->d_gptrs, grad_ptrs, n * sizeof(float *), hipMemcpyHostToDevice));
+        ctx->h_gptrs.assign(grad_ptrs, grad_ptrs + n);
+    }
+    DefStepArgs a = base_args(ctx, next_start(ctx));
+    a.g_flat = nullptr;
+    a.ldg = 0;
+    a.g_ptrs = ctx->d_gptrs;
+    return run_step(ctx, a, false, y_out);
+}
+
+int def_a_step_tensors(def_ctx *ctx, const float *const *grad_ptrs)
+{
+    return def_step_tensors(ctx, grad_ptrs, nullptr);
+}
+
+int def_output(def_ctx *ctx, float *y_out)
+{
+    if (!ctx || !y_out || (uintptr_t)y_out % 4 != 0) return DEF_EINVAL;
+    DefStepArgs a = base_args(ctx, 0);
+    DEF_HIP(def_launch_output(a, y_out, ctx->stream));
+    return DEF_OK;
+}
+
+int def_set_seed(def_ctx *ctx, uint64_t seed)
+{
+    if (!ctx) return DEF_EINVAL;
+    ctx->seed = seed;
+    return DEF_OK;
+}
+
+int def_set_lr(def_ctx *ctx, float lr)
+{
+    if (!ctx || !(lr == lr)) return DEF_EINVAL;
+    ctx->lr = lr;
+    return DEF_OK;
+}
+
+int def_set_step(def_ctx *ctx, uint64_t t)
+{
+    if (!ctx) return DEF_EINVAL;
+    ctx->t = t;
+    return DEF_OK;
+}
+
+int def_get_step(const def_ctx *ctx, uint64_t *t)
+{
+    if (!ctx || !t) return DEF_EINVAL;
+    *t = ctx->t;
+    return DEF_OK;
+}
+
+int def_force_next_start(def_ctx *ctx, int64_t s)
+{
+    if (!ctx) return DEF_EINVAL;
+    if (s >= 0 && (uint64_t)s >= ctx->d) return DEF_EINVAL;
+    ctx->forced = s < 0 ? -1 : s;
+    return DEF_OK;
+}
+
+int def_last_block(const def_ctx *ctx, uint64_t *start, uint64_t *len)
+{
+    if (!ctx || !ctx->has_last) return DEF_EINVAL;
+    if (start) *start = ctx->last_start;
+    if (len) *len = ctx->B;
+    return DEF_OK;
+}
+
+int def_state_ptrs(def_ctx *ctx, float **e, float **m, float **avg_block, uint64_t *ld_state)
+{
+    if (!ctx) return DEF_EINVAL;
+    if (e) *e = ctx->e;
+    if (m) *m = ctx->m;
+    if (avg_block) *avg_block = ctx->avg;
+    if (ld_state) *ld_state = ctx->ld;
+    return DEF_OK;
+}
+
+int def_last_path(const def_ctx *ctx, int *vectorised)
+{
+    if (!ctx || !vectorised || !ctx->has_last) return DEF_EINVAL;
+    *vectorised = ctx->last_vec;
+    return DEF_OK;
+}
+
+const char *def_last_kernel(const def_ctx *ctx)
+{
+    return ctx && ctx->has_last ? ctx->kernel_name : nullptr;
+}
+
+int def_profile_begin(def_ctx *ctx, uint32_t max_steps)
+{
+    if (!ctx || max_steps == 0 || max_steps > (1u << 20)) return DEF_EINVAL;
+    for (hipEvent_t ev : ctx->ev) (void)hipEventDestroy(ev);
+    ctx->ev.clear();
+    ctx->prof_cap = ctx->prof_n = 0;
+    try {
+        ctx->ev.reserve(2 * (size_t)max_steps);
+    } catch (const std::bad_alloc &) {
+        return DEF_ENOMEM;
+    }
+    for (uint32_t q = 0; q < 2 * max_steps; ++q) {
+        hipEvent_t ev;
+        DEF_HIP(hipEventCreate(&ev));
+        ctx->ev.push_back(ev);
+    }
+    ctx->prof_cap = max_steps;
+    return DEF_OK;
+}
+
+int def_profile_end(def_ctx *ctx, float *ms, uint32_t cap, uint32_t *n)
+{
+    if (!ctx || !n || (cap && !ms)) return DEF_EINVAL;
+    const uint32_t recorded = ctx->prof_n;
+    int rc = DEF_OK;
+    if (recorded) {
+        hipError_t err = hipEventSynchronize(ctx->ev[2 * recorded - 1]);
+        for (uint32_t q = 0; err == hipSuccess && q < recorded && q < cap; ++q)
+            err = hipEventElapsedTime(&ms[q], ctx->ev[2 * q], ctx->ev[2 * q + 1]);
+        if (err != hipSuccess) rc = hip_fail(err);
+    }
+    for (hipEvent_t ev : ctx->ev) (void)hipEventDestroy(ev);
+    ctx->ev.clear();
+    ctx->prof_cap = ctx->prof_n = 0;
+    *n = recorded;
+    return rc;
+}
+
+const char *def_strerror(int status)
+{
+    switch (status) {
+    case DEF_OK: return "ok";
+    case DEF_EINVAL: return "invalid argument";
+    case DEF_ENOMEM: return "out of memory";
+    case DEF_EHIP: return "HIP runtime error (see def_last_hip_error)";
+    default: return "unknown status";
+    }
+}
+
+int def_last_hip_error(void) { return g_last_hip_error; }
+
+}  // extern "C"

@@ -1,0 +1,72 @@
+// Internal interface between the host side of the library (def_api.hip) and
+// its kernels (def_kernels.hip).  Not part of the C ABI.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+// One work item of the element-wise streaming kernel: a run of consecutive flat
+// indices that lies inside one tensor of the model.
+struct DefChunk {
+    uint64_t start;   // first flat index
+    uint32_t len;     // 1..DEF_ELEM_CHUNK
+    uint32_t tensor;  // tensor the run belongs to
+};
+
+constexpr uint32_t DEF_ELEM_CHUNK = 2048;   // elements per chunk of the element-wise kernel
+constexpr uint32_t DEF_AVG_TILE = 256;      // block columns per workgroup of the averaging kernel
+constexpr uint32_t DEF_THREADS = 256;       // workgroup size of every kernel but the vectorised pass
+// Launch shape of the vectorised streaming kernel.  Measured on MI355X (d = 25.6 M,
+// W = 16): one wave per workgroup with one float4 group per lane beats every larger
+// tile (64x1: 78 % of the 8 TB/s HBM peak, 256x1: 75 %, 256x4: 73 %); stores
+// in particular lose bandwidth when a wave issues several of them back to back.
+constexpr uint32_t DEF_VEC_THREADS = 64;
+constexpr uint32_t DEF_VEC_QUADS = 1;       // float4 groups per thread
+// Tiles per super-tile of the blocked work-item order used with weight decay.  One
+// tile is 1 KiB of a row, so a super-tile covers 16 MiB of x; workgroups are dealt
+// round-robin to the 8 XCDs, so each XCD's 4 MiB L2 holds 2 MiB of x while the W
+// workers pass over it.  Measured (d = 25.6 M, W = 16, random data): 8192 -> 78.4 %,
+// 16384 -> 79.6 %, 32768 -> 75 % of the HBM peak (the piece no longer fits in L2).
+constexpr uint32_t DEF_SUPER_TILES = 16384;
+
+// Everything one step needs on the device.
+struct DefStepArgs {
+    // problem (notation of Algorithm 1 / Sec. 3.2 of arXiv 2004.05298)
+    uint64_t d;        // parameters
+    uint64_t B;        // block length
+    uint64_t s;        // block start s_t
+    uint32_t W;        // workers
+    float lr, mu, wd;  // eta, mu, weight decay
+    // library-owned state
+    float *e;          // [W][ld] error memory
+    float *m;          // [W][ld] momentum buffer (nullptr when mu == 0)
+    uint64_t ld;       // row stride of e and m, multiple of 64
+    float *msg;        // [W][ldmsg] compact compressed vectors C(p_k): entry j <-> index (s+j) mod d
+    uint64_t ldmsg;    // multiple of DEF_AVG_TILE
+    float *avg;        // [B] averaged block
+    // parameters x
+    float *x_flat;             // flat mode, else nullptr
+    float *const *x_ptrs;      // DEVICE table of L tensor pointers (tensor mode), else nullptr
+    const uint64_t *off;       // DEVICE offset table, L+1 entries
+    uint32_t L;
+    // gradients
+    const float *g_flat;       // flat mode: worker k at g_flat + k*ldg
+    uint64_t ldg;
+    const float *const *g_ptrs;  // DEVICE table [W][L] (tensor mode), else nullptr
+    // element-wise kernel work list
+    const DefChunk *chunks;
+    uint32_t n_chunks;
+};
+
+// Text describing the instantiation def_launch_stream_vec4 / _elem picks for these arguments.
+void def_describe_stream_kernel(const DefStepArgs &a, bool vec, char *out, size_t cap);
+// Fused momentum + error feedback + compress + residual pass, dwordx4 accesses.
+// Needs: g_flat 16-byte aligned, ldg % 4 == 0, x_flat (if wd != 0) 16-byte aligned.
+hipError_t def_launch_stream_vec4(const DefStepArgs &a, hipStream_t st);
+// Same pass, one dword per access, any alignment, flat or per-tensor pointers.
+hipError_t def_launch_stream_elem(const DefStepArgs &a, hipStream_t st);
+// Cross-worker average of the compact blocks (LDS-staged) and parameter update.
+hipError_t def_launch_average_update(const DefStepArgs &a, hipStream_t st);
+// y = x - mean_k e_k.
+hipError_t def_launch_output(const DefStepArgs &a, float *y, hipStream_t st);

@@ -1,0 +1,406 @@
+// HIP kernels (gfx950, wave64) for one DEF / DEF-A iteration with RBGS.
+//
+// Method: arXiv 2004.05298, Algorithm 1 with the momentum variant of Sec. 3.2.
+// For every worker k and flat index i
+//     m_k[i] <- mu*m_k[i] + g_k[i]                 (Sec. 3.2 "Momentum Variant")
+//     p       = eta*m_k[i] + e_k[i]                (Algorithm 1, error feedback)
+//     e_k[i] <- i in block ? +0 : p                (Algorithm 1, e <- p - C(p))
+//     msg_k[(i - s) mod d] = p  for i in block     (C(p_k), compact)
+// then  cbar[j] = (1/W) sum_k msg_k[j]             (Algorithm 1, all-reduce line)
+//       x[(s+j) mod d] -= cbar[j]                  (Algorithm 1, update line)
+// The block {(s+j) mod d : j < B} is the RBGS compressor of Sec. 1.
+//
+// Nothing here is a contraction: the step is a streaming pass of five 4-byte
+// accesses per (worker, index) and is bound by HBM bandwidth.  What the kernels
+// care about is therefore how requests reach memory: dwordx4 per lane (1 KiB of
+// consecutive bytes per wave instruction), non-temporal loads and stores for data
+// touched once per step, few accesses per wave so that loads and stores of many
+// waves interleave finely, work items numbered so that the chip sweeps each
+// worker row front to back, and a grid far larger than the 256 compute units.
+//
+// Arithmetic: every multiply and every add rounds once in binary32.  Fused
+// multiply-add would change results by an ulp, so contraction is switched off
+// for the whole file (and again on the compiler command line).
+#include "def_internal.h"
+
+#include <cstdio>
+
+#pragma clang fp contract(off)
+
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+namespace {
+
+template <bool NT>
+__device__ __forceinline__ v4f load4(const float *p)
+{
+    if constexpr (NT) return __builtin_nontemporal_load(reinterpret_cast<const v4f *>(p));
+    else return *reinterpret_cast<const v4f *>(p);
+}
+
+template <bool NT>
+__device__ __forceinline__ void store4(float *p, v4f v)
+{
+    if constexpr (NT) __builtin_nontemporal_store(v, reinterpret_cast<v4f *>(p));
+    else *reinterpret_cast<v4f *>(p) = v;
+}
+
+// The compensated value p_{k,t}[i]; updates m in place when momentum is on.
+template <bool HAS_MU, bool HAS_WD>
+__device__ __forceinline__ float compensated(float g, float &m, float e, float x,
+                                             float lr, float mu, float wd)
+{
+    float gp = g;
+    if constexpr (HAS_WD) {
+        const float decay = wd * x;      // weight decay folded into the gradient at x_t
+        gp = g + decay;
+    }
+    float mk = gp;
+    if constexpr (HAS_MU) {
+        const float carried = mu * m;
+        mk = carried + gp;               // m_{k,t+1} = mu*m_{k,t} + g_{k,t}
+        m = mk;
+    }
+    const float step = lr * mk;
+    return step + e;                     // p_{k,t} = eta*m_{k,t+1} + e_{k,t}
+}
+
+// Workgroup ids are dealt round-robin to the 8 XCDs.  Work items (one worker's
+// piece of one column tile) are numbered 0..tiles*W-1; MAP chooses how a
+// workgroup id becomes a work item:
+//   MAP_LINEAR_T  item = workgroup id, tile index fastest: each worker row is
+//               streamed front to back, one row after the other;
+//   MAP_LINEAR_K  item = workgroup id, worker index fastest;
+//   MAP_XCD_T / MAP_XCD_K  as above, but XCD c owns the contiguous item range
+//               [c*n/8, (c+1)*n/8);
+//   MAP_BLOCKED   the columns are cut into super-tiles of DEF_SUPER_TILES tiles;
+//               within a super-tile the workers follow one another, each
+//               streaming its piece of the super-tile front to back.  With
+//               weight decay all W workers read the same piece of x within a
+//               short time, so it is fetched from HBM once and then served by L2;
+//   MAP_XCD_BLOCKED  MAP_BLOCKED with XCD-contiguous item ranges.
+enum { MAP_XCD_K = 0, MAP_LINEAR_K = 1, MAP_LINEAR_T = 2, MAP_XCD_T = 3, MAP_BLOCKED = 4,
+       MAP_XCD_BLOCKED = 5 };
+
+template <int MAP>
+__device__ __forceinline__ bool decode_item(uint64_t total, uint64_t tiles, uint32_t W, uint32_t super,
+                                            uint32_t &k, uint64_t &tile)
+{
+    uint64_t item = blockIdx.x;
+    if constexpr (MAP == MAP_XCD_K || MAP == MAP_XCD_T || MAP == MAP_XCD_BLOCKED)
+        item = (uint64_t)(blockIdx.x & 7u) * (uint64_t)(gridDim.x >> 3) + (uint64_t)(blockIdx.x >> 3);
+    if (item >= total) return false;
+    if constexpr (MAP == MAP_XCD_K || MAP == MAP_LINEAR_K) {
+        k = (uint32_t)(item % W);
+        tile = item / W;
+    } else if constexpr (MAP == MAP_LINEAR_T || MAP == MAP_XCD_T) {
+        tile = item % tiles;
+        k = (uint32_t)(item / tiles);
+    } else {
+        const uint64_t per_super = (uint64_t)W * super;       // items of a full super-tile
+        const uint64_t sup = item / per_super;
+        const uint64_t rem = item - sup * per_super;
+        const uint64_t first = sup * super;                   // first tile of this super-tile
+        const uint64_t width = tiles - first < super ? tiles - first : super;   // last one may be short
+        k = (uint32_t)(rem / width);
+        tile = first + (rem - (uint64_t)k * width);
+    }
+    return true;
+}
+
+// ---------------------------------------------------------------------------
+// Streaming pass, vectorised.  One workgroup = one worker's tile of
+// THREADS*U float4 groups; thread t owns groups t, t+THREADS, ... so that each wave
+// instruction touches 1 KiB of consecutive memory.
+// ---------------------------------------------------------------------------
+template <bool HAS_MU, bool HAS_WD, int THREADS, int U, bool NT_LD, bool NT_ST, int MAP>
+__global__ __launch_bounds__(THREADS) void def_stream_vec4_kernel(DefStepArgs a, uint64_t tiles,
+                                                                  uint64_t total, uint32_t super)
+{
+    uint32_t k;
+    uint64_t tile;
+    if (!decode_item<MAP>(total, tiles, a.W, super, k, tile)) return;
+
+    const float *__restrict__ g = a.g_flat + (uint64_t)k * a.ldg;
+    float *__restrict__ e = a.e + (uint64_t)k * a.ld;
+    float *__restrict__ m = HAS_MU ? a.m + (uint64_t)k * a.ld : nullptr;
+    float *__restrict__ msg = a.msg + (uint64_t)k * a.ldmsg;
+    const float *__restrict__ x = a.x_flat;
+
+    constexpr uint64_t STRIDE = THREADS * 4;             // elements between a thread's groups
+    const uint64_t i_first = (tile * (uint64_t)(THREADS * U) + threadIdx.x) * 4;
+    const uint64_t tile_end = (tile + 1) * (uint64_t)(THREADS * U) * 4;
+    const bool interior = tile_end <= a.d;
+
+    v4f gv[U], mv[U], ev[U], xv[U];
+    if (interior) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const uint64_t i = i_first + u * STRIDE;
+            gv[u] = load4<NT_LD>(g + i);
+            if constexpr (HAS_MU) mv[u] = load4<NT_LD>(m + i);
+            ev[u] = load4<NT_LD>(e + i);
+            if constexpr (HAS_WD) xv[u] = load4<false>(x + i);
+        }
+    } else {
+        // last tile of the row: a group may be cut by d or lie beyond it.  The
+        // state rows are padded to a multiple of 64, so e and m can always be
+        // read as whole groups; g and x are read element by element at the cut.
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const uint64_t i = i_first + u * STRIDE;
+            gv[u] = (v4f)(0.0f); mv[u] = (v4f)(0.0f); ev[u] = (v4f)(0.0f); xv[u] = (v4f)(0.0f);
+            if (i + 4 <= a.d) {
+                gv[u] = load4<NT_LD>(g + i);
+                if constexpr (HAS_WD) xv[u] = load4<false>(x + i);
+            } else if (i < a.d) {
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+                    if (i + c < a.d) {
+                        gv[u][c] = g[i + c];
+                        if constexpr (HAS_WD) xv[u][c] = x[i + c];
+                    }
+            }
+            if (i < a.d) {
+                if constexpr (HAS_MU) mv[u] = load4<NT_LD>(m + i);
+                ev[u] = load4<NT_LD>(e + i);
+            }
+        }
+    }
+
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const uint64_t i = i_first + u * STRIDE;
+        if (!interior && i >= a.d) continue;
+        v4f p;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            float mc = HAS_MU ? mv[u][c] : 0.0f;
+            p[c] = compensated<HAS_MU, HAS_WD>(gv[u][c], mc, ev[u][c], HAS_WD ? xv[u][c] : 0.0f,
+                                               a.lr, a.mu, a.wd);
+            if constexpr (HAS_MU) mv[u][c] = mc;
+        }
+        // position of element i inside the circular block: j = (i - s) mod d
+        uint64_t j0 = i >= a.s ? i - a.s : i + a.d - a.s;
+        v4f en = p;                                           // off-block: e <- p
+        if (!(j0 >= a.B && j0 + 3 < a.d)) {                   // some element may be kept
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                uint64_t j = j0 + c;
+                if (j >= a.d) j -= a.d;
+                if (i + c < a.d && j < a.B) {
+                    msg[j] = p[c];                            // C(p_k), compact
+                    en[c] = 0.0f;                             // p - C(p) = +0 inside the block
+                }
+            }
+        }
+        if constexpr (HAS_MU) store4<NT_ST>(m + i, mv[u]);
+        store4<NT_ST>(e + i, en);
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Streaming pass, one dword per access.  Accepts any alignment and per-tensor
+// gradient / parameter pointers; the host cuts the flat index range into chunks
+// that never cross a tensor boundary.
+// ---------------------------------------------------------------------------
+template <bool HAS_MU, bool HAS_WD>
+__global__ __launch_bounds__(DEF_THREADS) void def_stream_elem_kernel(DefStepArgs a, uint64_t total)
+{
+    uint32_t k;
+    uint64_t chunk;
+    if (!decode_item<MAP_XCD_K>(total, a.n_chunks, a.W, 0, k, chunk)) return;
+    const DefChunk ch = a.chunks[chunk];
+    const uint64_t local = ch.start - a.off[ch.tensor];       // offset inside the tensor
+
+    const float *__restrict__ g = a.g_ptrs ? a.g_ptrs[(uint64_t)k * a.L + ch.tensor] + local
+                                           : a.g_flat + (uint64_t)k * a.ldg + ch.start;
+    const float *__restrict__ x = nullptr;
+    if constexpr (HAS_WD) x = a.x_ptrs ? a.x_ptrs[ch.tensor] + local : a.x_flat + ch.start;
+    float *__restrict__ e = a.e + (uint64_t)k * a.ld + ch.start;
+    float *__restrict__ m = HAS_MU ? a.m + (uint64_t)k * a.ld + ch.start : nullptr;
+    float *__restrict__ msg = a.msg + (uint64_t)k * a.ldmsg;
+
+    constexpr int PER = DEF_ELEM_CHUNK / DEF_THREADS;
+    float gv[PER], mv[PER], ev[PER], xv[PER];
+#pragma unroll
+    for (int u = 0; u < PER; ++u) {
+        const uint32_t o = threadIdx.x + u * DEF_THREADS;
+        gv[u] = 0.0f; mv[u] = 0.0f; ev[u] = 0.0f; xv[u] = 0.0f;
+        if (o < ch.len) {
+            gv[u] = g[o];
+            if constexpr (HAS_MU) mv[u] = m[o];
+            ev[u] = e[o];
+            if constexpr (HAS_WD) xv[u] = x[o];
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < PER; ++u) {
+        const uint32_t o = threadIdx.x + u * DEF_THREADS;
+        if (o >= ch.len) continue;
+        float mc = mv[u];
+        const float p = compensated<HAS_MU, HAS_WD>(gv[u], mc, ev[u], xv[u], a.lr, a.mu, a.wd);
+        const uint64_t i = ch.start + o;
+        const uint64_t j = i >= a.s ? i - a.s : i + a.d - a.s;
+        float en = p;
+        if (j < a.B) {
+            msg[j] = p;
+            en = 0.0f;
+        }
+        if constexpr (HAS_MU) m[o] = mc;
+        e[o] = en;
+    }
+}
+
+// Address of parameter i: flat vector, or tensor table + offset table.
+__device__ __forceinline__ float *param_addr(const DefStepArgs &a, uint64_t i)
+{
+    if (a.x_flat) return a.x_flat + i;
+    uint32_t lo = 0, hi = a.L;                                // off[lo] <= i < off[hi]
+    while (hi - lo > 1) {
+        const uint32_t mid = (lo + hi) >> 1;
+        if (a.off[mid] <= i) lo = mid; else hi = mid;
+    }
+    return a.x_ptrs[lo] + (i - a.off[lo]);
+}
+
+// ---------------------------------------------------------------------------
+// Cross-worker average of the compact blocks and parameter update.  This is
+// the on-one-GPU stand-in for the ring all-reduce of Algorithm 1.
+// One workgroup = 256 block columns.  The four waves stage worker rows through
+// LDS, one row per wave at a time, each lane loading a float4 (1 KiB coalesced
+// per row); after the barrier thread c adds column c over the workers in order
+// k = 0, 1, ..., W-1 starting from +0, so the sum is the plain left-to-right sum
+// whatever the launch shape.
+// ---------------------------------------------------------------------------
+constexpr int AVG_ROWS = 16;
+
+__global__ __launch_bounds__(DEF_THREADS) void def_average_update_kernel(DefStepArgs a)
+{
+    __shared__ float stage[AVG_ROWS][DEF_AVG_TILE];
+    const uint64_t j_tile = (uint64_t)blockIdx.x * DEF_AVG_TILE;
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t wave = threadIdx.x >> 6;
+
+    float acc = 0.0f;
+    for (uint32_t k0 = 0; k0 < a.W; k0 += AVG_ROWS) {
+        const uint32_t rows = min((uint32_t)AVG_ROWS, a.W - k0);
+        for (uint32_t r = wave; r < rows; r += DEF_THREADS / 64) {
+            const float *row = a.msg + (uint64_t)(k0 + r) * a.ldmsg + j_tile;   // rows padded to the tile
+            *reinterpret_cast<v4f *>(&stage[r][lane * 4]) = load4<false>(row + lane * 4);
+        }
+        __syncthreads();
+        for (uint32_t r = 0; r < rows; ++r) acc = acc + stage[r][threadIdx.x];
+        __syncthreads();
+    }
+    const uint64_t j = j_tile + threadIdx.x;
+    if (j < a.B) {
+        const float cbar = acc / (float)a.W;                  // (1/W) sum_k C(p_k)
+        a.avg[j] = cbar;
+        uint64_t i = a.s + j;
+        if (i >= a.d) i -= a.d;
+        float *px = param_addr(a, i);
+        *px = *px - cbar;                                     // x_{t+1} = x_t - C(p_t)
+    }
+}
+
+// ---------------------------------------------------------------------------
+// DEF output y = x - (1/W) sum_k e_k (Algorithm 1 "Output").  One thread owns
+// four consecutive columns and walks the workers in order.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(DEF_THREADS) void def_output_kernel(DefStepArgs a, float *y, int vec_xy)
+{
+    const uint64_t i = ((uint64_t)blockIdx.x * DEF_THREADS + threadIdx.x) * 4;
+    if (i >= a.d) return;
+    v4f acc = (v4f)(0.0f);
+#pragma unroll 8
+    for (uint32_t k = 0; k < a.W; ++k) acc = acc + load4<false>(a.e + (uint64_t)k * a.ld + i);
+    const v4f mean = acc / (float)a.W;
+    if (vec_xy && i + 4 <= a.d) {
+        store4<false>(y + i, load4<false>(a.x_flat + i) - mean);
+    } else {
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+            if (i + c < a.d) y[i + c] = *param_addr(a, i + c) - mean[c];
+    }
+}
+
+uint32_t grid_for(uint64_t total)
+{
+    return (uint32_t)((total + 7) / 8 * 8);                   // the XCD maps need a multiple of 8
+}
+
+}  // namespace
+
+void def_describe_stream_kernel(const DefStepArgs &a, bool vec, char *out, size_t cap)
+{
+    const int mu = a.mu != 0.0f, wd = a.wd != 0.0f;
+    if (vec) {
+        char order[32];
+        if (wd) std::snprintf(order, sizeof order, "blocked:%u", DEF_SUPER_TILES);
+        else std::snprintf(order, sizeof order, "linear");
+        std::snprintf(out, cap, "def_stream_vec4_kernel<mu=%d,wd=%d,threads=%u,quads=%u,nt=1,order=%s>",
+                      mu, wd, DEF_VEC_THREADS, DEF_VEC_QUADS, order);
+    } else {
+        std::snprintf(out, cap, "def_stream_elem_kernel<mu=%d,wd=%d,threads=%u,chunk=%u>", mu, wd,
+                      DEF_THREADS, DEF_ELEM_CHUNK);
+    }
+}
+
+hipError_t def_launch_stream_vec4(const DefStepArgs &a, hipStream_t st)
+{
+    constexpr int U = DEF_VEC_QUADS, T = DEF_VEC_THREADS;
+    // Non-temporal loads and stores for the three streams: they are touched once
+    // per step, and keeping them out of L2 / Infinity Cache is worth +20 % here.
+    constexpr bool NL = true, NS = true;
+    const uint64_t per_tile = (uint64_t)T * U * 4;
+    const uint64_t tiles = (a.d + per_tile - 1) / per_tile;
+    const uint64_t total = tiles * a.W;
+    if (total > 0x7fffffffull - 8) return hipErrorInvalidConfiguration;
+    const dim3 grid(grid_for(total)), block(T);
+    const bool mu = a.mu != 0.0f, wd = a.wd != 0.0f;
+    // Without weight decay nothing is shared between workers and the plain
+    // row-after-row sweep is fastest.  With weight decay every worker reads x: the
+    // blocked order lets all W workers pass over a piece of x while it sits in L2,
+    // so x is fetched from HBM once per step instead of W times.
+    if (mu && wd)
+        def_stream_vec4_kernel<true, true, T, U, NL, NS, MAP_BLOCKED><<<grid, block, 0, st>>>(a, tiles, total, DEF_SUPER_TILES);
+    else if (mu)
+        def_stream_vec4_kernel<true, false, T, U, NL, NS, MAP_LINEAR_T><<<grid, block, 0, st>>>(a, tiles, total, 0);
+    else if (wd)
+        def_stream_vec4_kernel<false, true, T, U, NL, NS, MAP_BLOCKED><<<grid, block, 0, st>>>(a, tiles, total, DEF_SUPER_TILES);
+    else
+        def_stream_vec4_kernel<false, false, T, U, NL, NS, MAP_LINEAR_T><<<grid, block, 0, st>>>(a, tiles, total, 0);
+    return hipGetLastError();
+}
+
+hipError_t def_launch_stream_elem(const DefStepArgs &a, hipStream_t st)
+{
+    const uint64_t total = (uint64_t)a.n_chunks * a.W;
+    if (total > 0x7fffffffull - 8) return hipErrorInvalidConfiguration;
+    const dim3 grid(grid_for(total)), block(DEF_THREADS);
+    const bool mu = a.mu != 0.0f, wd = a.wd != 0.0f;
+    if (mu && wd) def_stream_elem_kernel<true, true><<<grid, block, 0, st>>>(a, total);
+    else if (mu) def_stream_elem_kernel<true, false><<<grid, block, 0, st>>>(a, total);
+    else if (wd) def_stream_elem_kernel<false, true><<<grid, block, 0, st>>>(a, total);
+    else def_stream_elem_kernel<false, false><<<grid, block, 0, st>>>(a, total);
+    return hipGetLastError();
+}
+
+hipError_t def_launch_average_update(const DefStepArgs &a, hipStream_t st)
+{
+    const uint64_t tiles = (a.B + DEF_AVG_TILE - 1) / DEF_AVG_TILE;
+    if (tiles > 0x7fffffffull) return hipErrorInvalidConfiguration;
+    def_average_update_kernel<<<dim3((uint32_t)tiles), dim3(DEF_THREADS), 0, st>>>(a);
+    return hipGetLastError();
+}
+
+hipError_t def_launch_output(const DefStepArgs &a, float *y, hipStream_t st)
+{
+    const uint64_t quads = (a.d + 3) / 4;
+    const uint64_t blocks = (quads + DEF_THREADS - 1) / DEF_THREADS;
+    if (blocks > 0x7fffffffull) return hipErrorInvalidConfiguration;
+    const int vec_xy = a.x_flat != nullptr && ((uintptr_t)a.x_flat % 16 == 0) && ((uintptr_t)y % 16 == 0);
+    def_output_kernel<<<dim3((uint32_t)blocks), dim3(DEF_THREADS), 0, st>>>(a, y, vec_xy);
+    return hipGetLastError();
+}

@@ -283,3 +283,34 @@ def gradient_set(w: Workload, slot: int, ld: Optional[int] = None, threads: int 
 
 def gradient_pool(w: Workload, ld: Optional[int] = None, threads: int = 8) -> List[np.ndarray]:
     return [gradient_set(w, slot, ld, threads) for slot in range(w.pool)]
+
+
+def padded_ld(d: int, multiple: int = 64) -> int:
+    """Row stride for a worker-major gradient buffer: d rounded up so that every
+    row starts 16-byte aligned."""
+    return -(-d // multiple) * multiple
+
+
+def device_gradient_pool(w: Workload, ld: int, device="cuda", threads: int = 16):
+    """The same gradient sets as gradient_pool(), generated row by row on the host
+    and copied straight into device tensors [W][ld], so that the host never holds
+    more than `threads` rows (the VGG-16-shaped set is 17.7 GB)."""
+    import torch
+
+    sigma_flat = None
+    if w.grad_kind == "per_tensor_sigma":
+        sigma_flat = np.repeat(per_tensor_sigma(w), np.asarray(w.tensor_sizes))
+    pool = []
+    for slot in range(w.pool):
+        dev = torch.empty((w.W, ld), dtype=torch.float32, device=device)
+
+        def make_row(k, slot=slot):
+            row = np.empty(ld, dtype=np.float32)
+            _fill_row(w, slot, k, row, sigma_flat)
+            return k, row
+
+        with ThreadPoolExecutor(max_workers=max(1, min(threads, w.W))) as ex:
+            for k, row in ex.map(make_row, range(w.W)):
+                dev[k].copy_(torch.from_numpy(row))
+        pool.append(dev)
+    return pool

@@ -1,0 +1,163 @@
+"""GPU parity at the full sizes of the model-shaped configurations, in the launch
+configuration the benchmark times (flat gradients, padded row stride, vectorised
+kernel).
+
+The two smaller configurations are compared buffer for buffer with the plain C
+oracle.  For the two largest, the oracle simulates a sample of columns exactly
+(each column of (x, e, m) evolves independently once the block of every step is
+known): random columns plus every tensor boundary, the ends of the vector, and
+the edges of every step's block; whole-buffer properties (zeroing of the last
+block, zero padding) are checked on the device.
+"""
+from __future__ import annotations
+
+import numpy as np
+import pytest
+
+from oracle.c_oracle import DefOracleC
+from oracle.philox import block_start
+from paper_2004_05298_amd import workloads as wl
+from tests.parity import assert_close, bit_equal, bits, in_block_mask
+
+pytestmark = pytest.mark.gpu
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def dev():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    torch.cuda.set_device(0)
+    return torch.device("cuda:0")
+
+
+def _ctx(w, x_dev):
+    from paper_2004_05298_amd import binding
+    binding.load_library()
+    return binding.DefContext(w.d, w.W, w.R, w.lr, w.momentum, w.weight_decay, w.seed,
+                              params=x_dev, tensor_offsets=w.tensor_offsets(),
+                              stream=torch.cuda.current_stream().cuda_stream)
+
+
+def _gpu_step(ctx, w, t, g, ld, y):
+    start = w.forced_start(t)
+    if start is not None:
+        ctx.force_next_start(start)
+    use_a = w.variant == "def_a" or (w.variant == "both" and t % 2 == 1)
+    if use_a:
+        ctx.a_step(g, ld)
+    else:
+        ctx.step(g, ld, y)
+    return start
+
+
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("name", ["resnet56_shaped", "resnet18_shaped"])
+def test_whole_buffers_against_c_oracle(dev, name):
+    w = wl.by_name(name)
+    d, W, ld = w.d, w.W, wl.padded_ld(w.d)
+    x0 = wl.initial_params(w)
+    host_pool = wl.gradient_pool(w, ld=ld, threads=16)
+    dev_pool = [torch.from_numpy(g).to(dev) for g in host_pool]
+    x = torch.from_numpy(x0).to(dev)
+    y = torch.empty(d, dtype=torch.float32, device=dev)
+    ora = DefOracleC(x0, W, w.R, w.lr, w.momentum, w.weight_decay, w.seed)
+    ctx = _ctx(w, x)
+    try:
+        for t in range(w.T):
+            last = t == w.T - 1
+            start = _gpu_step(ctx, w, t, dev_pool[t % w.pool], ld, y if last else None)
+            s = ora.step(host_pool[t % w.pool], start=start)
+            assert ctx.last_block() == (s, w.B)
+        torch.cuda.synchronize()
+        assert ctx.last_path_vectorised()
+        e, m, avg = ctx.state_tensors()
+        e, m, avg = e.cpu().numpy(), m.cpu().numpy(), avg.cpu().numpy()
+        xg = x.cpu().numpy()
+        assert_close("x", xg, ora.x)
+        assert_close("e", e[:, :d], ora.e)
+        assert_close("m", m[:, :d], ora.m)
+        assert_close("averaged block", avg, ora.compact_block())
+        mask = in_block_mask(d, ora.last_start, w.B)
+        assert (bits(e[:, :d][:, mask]) == 0).all()
+        assert np.array_equal(e[:, :d] == 0, ora.e == 0)
+        assert not e[:, d:].any() and not m[:, d:].any()
+        if w.variant != "def_a":
+            assert_close("y", y.cpu().numpy(), ora.y())
+        else:
+            ctx.output(y)
+            torch.cuda.synchronize()
+            assert_close("y", y.cpu().numpy(), ora.y())
+        print(f"[fullsize] {name}: bit-identical x={bit_equal(xg, ora.x)} e={bit_equal(e[:, :d], ora.e)} "
+              f"m={bit_equal(m[:, :d], ora.m)} avg={bit_equal(avg, ora.compact_block())}", flush=True)
+        assert bit_equal(e[:, :d], ora.e) and bit_equal(m[:, :d], ora.m)
+    finally:
+        ctx.destroy()
+
+
+def _sample_columns(w, starts, n_random):
+    d, B = w.d, w.B
+    rng = np.random.default_rng([w.seed, 99])
+    picks = [rng.integers(0, d, size=n_random), np.arange(0, min(d, 64)), np.arange(max(0, d - 64), d)]
+    off = w.tensor_offsets().astype(np.int64)
+    for delta in range(-2, 3):
+        picks.append(np.clip(off + delta, 0, d - 1))
+    for s in starts:
+        for edge in (s, s + B):
+            picks.append((edge + np.arange(-4, 5)) % d)
+    return np.unique(np.concatenate(picks).astype(np.int64))
+
+
+@pytest.mark.timeout(900)
+@pytest.mark.parametrize("name", ["resnet50_shaped", "vgg16_shaped"])
+def test_sampled_columns_at_full_size(dev, name):
+    w = wl.by_name(name)
+    d, W, ld = w.d, w.W, wl.padded_ld(w.d)
+    print(f"[fullsize] {name}: generating {w.pool} gradient sets of {W}x{d}", flush=True)
+    dev_pool = wl.device_gradient_pool(w, ld, device=dev)
+    x0 = wl.initial_params(w)
+    starts = [w.forced_start(t) if w.forced_start(t) is not None else block_start(w.seed, t, d)
+              for t in range(w.T)]
+    cols = _sample_columns(w, starts, 1_000_000)
+    cols_dev = torch.from_numpy(cols).to(dev)
+    host_cols = [g.index_select(1, cols_dev).cpu().numpy() for g in dev_pool]
+    ora = DefOracleC(x0[cols], W, w.R, w.lr, w.momentum, w.weight_decay, w.seed, d=d, index=cols)
+    x = torch.from_numpy(x0).to(dev)
+    y = torch.empty(d, dtype=torch.float32, device=dev)
+    ctx = _ctx(w, x)
+    try:
+        for t in range(w.T):
+            last = t == w.T - 1
+            start = _gpu_step(ctx, w, t, dev_pool[t % w.pool], ld, y if last else None)
+            s = ora.step(host_cols[t % w.pool], start=start)
+            assert ctx.last_block() == (s, w.B) and s == starts[t]
+        torch.cuda.synchronize()
+        assert ctx.last_path_vectorised()
+        e, m, avg = ctx.state_tensors()
+        xg = x.index_select(0, cols_dev).cpu().numpy()
+        eg = e.index_select(1, cols_dev).cpu().numpy()
+        mg = m.index_select(1, cols_dev).cpu().numpy()
+        assert_close("x[cols]", xg, ora.x)
+        assert_close("e[cols]", eg, ora.e)
+        assert_close("m[cols]", mg, ora.m)
+        assert np.array_equal(eg == 0, ora.e == 0)
+        # the averaged block at the sampled positions that fall inside the last block
+        s_last = starts[-1]
+        j = (cols - s_last) % d
+        inside = j < w.B
+        avg_g = avg.index_select(0, torch.from_numpy(j[inside]).to(dev)).cpu().numpy()
+        assert_close("averaged block[cols]", avg_g, ora.last_cbar_dense[inside])
+        # y is produced on the steps that take def_step; recompute it for the final state
+        ctx.output(y)
+        torch.cuda.synchronize()
+        assert_close("y[cols]", y.index_select(0, cols_dev).cpu().numpy(), ora.y())
+        # whole-buffer properties, on the device
+        first = min(w.B, d - s_last)
+        assert not e[:, s_last:s_last + first].any() and not e[:, :w.B - first].any(), "last block not zero"
+        assert not e[:, d:].any() and not m[:, d:].any(), "padding touched"
+        assert torch.isfinite(x).all()
+        print(f"[fullsize] {name}: {cols.size} columns, bit-identical x={bit_equal(xg, ora.x)} "
+              f"e={bit_equal(eg, ora.e)} m={bit_equal(mg, ora.m)}", flush=True)
+        assert bit_equal(eg, ora.e) and bit_equal(mg, ora.m)
+    finally:
+        ctx.destroy()

@@ -1,0 +1,338 @@
+"""GPU parity: the HIP library, called through its C ABI, against the CPU oracle
+on identical seeded inputs.  Every test here needs a real MI355X."""
+from __future__ import annotations
+
+import numpy as np
+import pytest
+
+from oracle.c_oracle import DefOracleC
+from oracle.def_oracle import DefOracle
+from paper_2004_05298_amd import workloads as wl
+from tests.parity import assert_close, bit_equal, bits, in_block_mask
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def dev():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    torch.cuda.set_device(0)
+    return torch.device("cuda:0")
+
+
+def _binding():
+    from paper_2004_05298_amd import binding
+    binding.load_library()          # raises if the HIP library is not built: no fallback
+    return binding
+
+
+def fetch_state(ctx, W, d):
+    torch.cuda.synchronize()
+    e, m, _ = ctx.state_tensors()
+    return e.cpu().numpy(), (m.cpu().numpy() if m is not None else None), e.shape[1]
+
+
+def fetch_avg(ctx):
+    torch.cuda.synchronize()
+    return ctx.state_tensors()[2].cpu().numpy()
+
+
+def run_case(dev, w, *, weight_decay=None, momentum=None, T=None, flat_params=True,
+             mode="flat", misalign=0, ld=None, oracle="np", check_every_step=True,
+             with_y=True, special=None, variant=None, forced=None):
+    """Run T steps on both sides and compare.  mode: "flat" (one gradient buffer
+    [W][ld]) or "tensors" (one allocation per worker and tensor)."""
+    binding = _binding()
+    wd = w.weight_decay if weight_decay is None else weight_decay
+    mu = w.momentum if momentum is None else momentum
+    T = w.T if T is None else T
+    variant = variant or w.variant
+    d, W = w.d, w.W
+    off = w.tensor_offsets()
+    ld = wl.padded_ld(d) if ld is None else ld
+    x0 = wl.initial_params(w)
+    pool = [g[:, :d] for g in wl.gradient_pool(w, ld=d, threads=4)]
+    if special is not None:
+        special(pool, x0)
+
+    # device inputs
+    if flat_params:
+        x_dev = torch.from_numpy(x0).to(dev)
+        params, param_tensors = x_dev, None
+    else:
+        param_tensors = [torch.from_numpy(x0[int(off[l]):int(off[l + 1])].copy()).to(dev)
+                         for l in range(w.n_tensors)]
+        params = None
+    if mode == "flat":
+        gdev = []
+        for g in pool:
+            buf = torch.zeros(W * ld + 8, dtype=torch.float32, device=dev)
+            view = buf[misalign:misalign + W * ld].view(W, ld)
+            view[:, :d].copy_(torch.from_numpy(np.ascontiguousarray(g)))
+            gdev.append((buf, view))
+    else:
+        gdev = []
+        for g in pool:
+            tensors = []
+            for k in range(W):
+                for l in range(w.n_tensors):
+                    a, b = int(off[l]), int(off[l + 1])
+                    # odd extra offset so that tensors start at every 4-byte alignment
+                    pad = (k + l) % 4
+                    buf = torch.zeros(b - a + pad, dtype=torch.float32, device=dev)
+                    buf[pad:].copy_(torch.from_numpy(np.ascontiguousarray(g[k, a:b])))
+                    tensors.append(buf[pad:])
+            gdev.append(tensors)
+    y_dev = torch.full((d,), float("nan"), dtype=torch.float32, device=dev)
+
+    if oracle == "np":
+        ora = DefOracle(x0, W, w.R, w.lr, mu, wd, w.seed)
+    else:
+        ora = DefOracleC(x0, W, w.R, w.lr, mu, wd, w.seed)
+
+    stream = torch.cuda.current_stream().cuda_stream
+    ctx = binding.DefContext(d, W, w.R, w.lr, mu, wd, w.seed, params=params,
+                             param_tensors=param_tensors, tensor_offsets=off, stream=stream)
+    exact = {}
+    try:
+        e_ptr, m_ptr, a_ptr, ld_state = ctx.state_ptrs()
+        assert ld_state >= d and ld_state % 64 == 0
+        assert (m_ptr != 0) == (mu != 0)
+        for t in range(T):
+            g_host = pool[t % w.pool]
+            start = (forced or w.forced_start)(t)
+            if start is not None:
+                ctx.force_next_start(start)
+            want_y = with_y and variant != "def_a" and (t == T - 1 or t == T // 2)
+            if mode == "flat":
+                view = gdev[t % w.pool][1]
+                if variant == "def_a":
+                    ctx.a_step(view, ld)
+                else:
+                    ctx.step(view, ld, y_dev if want_y else None)
+            else:
+                if variant == "def_a":
+                    ctx.a_step_tensors(gdev[t % w.pool])
+                else:
+                    ctx.step_tensors(gdev[t % w.pool], y_dev if want_y else None)
+            s = ora.step(g_host, start=start)
+            # integer results: bit-exact
+            assert ctx.last_block() == (s, w.B), (t, ctx.last_block(), s, w.B)
+            assert ctx.get_step() == t + 1
+            if check_every_step or t == T - 1:
+                torch.cuda.synchronize()
+                avg = fetch_avg(ctx)
+                assert_close(f"averaged block t={t}", avg, ora.compact_block())
+                exact.setdefault("avg", True)
+                exact["avg"] &= bit_equal(avg, ora.compact_block())
+                e, m, _ = fetch_state(ctx, W, d)
+                mask = in_block_mask(d, s, w.B)
+                # error-memory zeroing: literal +0 inside the block, for every worker
+                assert (bits(e[:, :d][:, mask]) == 0).all(), f"t={t}: block not zeroed"
+                assert not e[:, d:].any(), "padding columns of e must stay zero"
+                if want_y:
+                    assert_close(f"y t={t}", y_dev.cpu().numpy(), ora.y())
+                    exact.setdefault("y", True)
+                    exact["y"] &= bit_equal(y_dev.cpu().numpy(), ora.y())
+        torch.cuda.synchronize()
+        if mode == "flat":
+            assert ctx.last_path_vectorised() == (misalign % 4 == 0 and ld % 4 == 0
+                                                  and (flat_params or wd == 0))
+        else:
+            assert not ctx.last_path_vectorised()
+        e, m, _ = fetch_state(ctx, W, d)
+        if flat_params:
+            x = x_dev.cpu().numpy()
+        else:
+            x = np.concatenate([p.cpu().numpy() for p in param_tensors])
+        assert_close("x", x, ora.x)
+        assert_close("e", e[:, :d], ora.e)
+        assert np.array_equal(e[:, :d] == 0, ora.e == 0), "zero pattern of e differs"
+        exact["x"], exact["e"] = bit_equal(x, ora.x), bit_equal(e[:, :d], ora.e)
+        if mu != 0:
+            assert_close("m", m[:, :d], ora.m)
+            assert not m[:, d:].any()
+            exact["m"] = bit_equal(m[:, :d], ora.m)
+        if variant != "def_a":
+            ctx.output(y_dev)
+            torch.cuda.synchronize()
+            assert_close("y (def_output)", y_dev.cpu().numpy(), ora.y())
+    finally:
+        ctx.destroy()
+    print(f"[parity] {w.name} mode={mode} misalign={misalign} wd={wd} mu={mu} T={T}: bit-identical {exact}",
+          flush=True)
+    return exact
+
+
+# --------------------------------------------------------------------------- #
+# The tiny configuration, exactly as specified: d=65,536, W=4, R=16, T=10.
+# --------------------------------------------------------------------------- #
+def test_tiny_configuration(dev):
+    w = wl.tiny()
+    assert (w.d, w.W, w.R, w.B, w.T) == (65536, 4, 16, 4096, 10)
+    exact = run_case(dev, w)
+    assert all(exact.values()), exact
+
+
+# --------------------------------------------------------------------------- #
+# Small relatives of the model-shaped configurations: ragged tensors, d not a
+# multiple of 4, several tiles of 4096 elements plus a ragged tail.
+# --------------------------------------------------------------------------- #
+SHRUNK = [
+    ("resnet56_shaped", 53018 + 2, 57, None, 12),
+    ("resnet18_shaped", 40009, 62, None, 10),
+    ("resnet50_shaped", 45057, 161, None, 10),
+    ("vgg16_shaped", 70003, 32, None, 12),
+]
+
+
+@pytest.mark.parametrize("name,d,L,W,T", SHRUNK, ids=[s[0] for s in SHRUNK])
+def test_shrunk_model_shaped(dev, name, d, L, W, T):
+    base = wl.by_name(name)
+    w = wl.shrunk(base, d=d, n_tensors=L, W=W, T=T, pool=min(base.pool, 4))
+    exact = run_case(dev, w)
+    assert exact["x"] and exact["e"] and exact.get("m", True), exact
+
+
+@pytest.mark.parametrize("name,d,L,W,T", SHRUNK, ids=[s[0] for s in SHRUNK])
+def test_shrunk_tensor_mode(dev, name, d, L, W, T):
+    """Per-tensor gradient and parameter allocations through the offset table."""
+    base = wl.by_name(name)
+    w = wl.shrunk(base, d=d, n_tensors=L, W=min(base.W, 8), T=6, pool=2)
+    exact = run_case(dev, w, mode="tensors", flat_params=False)
+    assert exact["x"] and exact["e"], exact
+
+
+@pytest.mark.parametrize("misalign,ld_extra", [(1, 0), (2, 3), (0, 1), (3, 2)])
+def test_unaligned_flat_gradients_take_elementwise_path(dev, misalign, ld_extra):
+    base = wl.resnet50_shaped()
+    w = wl.shrunk(base, d=30011, n_tensors=9, W=5, T=6, pool=2)
+    exact = run_case(dev, w, misalign=misalign, ld=w.d + ld_extra)
+    assert exact["x"] and exact["e"] and exact["m"], exact
+
+
+def test_flat_gradients_with_tensor_params(dev):
+    base = wl.resnet18_shaped()
+    w = wl.shrunk(base, d=25003, n_tensors=11, W=6, T=6, pool=2)
+    for wd in (0.0, 1e-3):
+        exact = run_case(dev, w, flat_params=False, weight_decay=wd, variant="def")
+        assert exact["x"] and exact["e"], exact
+
+
+# --------------------------------------------------------------------------- #
+# Degenerate shapes and hyper-parameters.
+# --------------------------------------------------------------------------- #
+@pytest.mark.parametrize("d,W,R", [
+    (1, 1, 1), (3, 2, 3), (4, 3, 1), (5, 1, 2), (63, 4, 63), (64, 2, 64), (257, 33, 5),
+    (4096, 17, 4096), (4097, 16, 1), (8191, 3, 2), (16384, 1, 7), (12289, 40, 3),
+])
+def test_degenerate_shapes(dev, d, W, R):
+    base = wl.tiny()
+    w = wl.shrunk(base, d=d, n_tensors=min(3, d), W=W, R=R, T=5, pool=3)
+    exact = run_case(dev, w, weight_decay=1e-3)
+    assert all(exact.values()), exact
+
+
+@pytest.mark.parametrize("mu,wd", [(0.0, 0.0), (0.0, 1e-2), (0.9, 0.0), (0.5, 5e-4)])
+@pytest.mark.parametrize("mode", ["flat", "tensors"])
+def test_hyperparameter_paths(dev, mu, wd, mode):
+    base = wl.resnet56_shaped()
+    w = wl.shrunk(base, d=20001, n_tensors=7, W=3, T=8, pool=3)
+    exact = run_case(dev, w, momentum=mu, weight_decay=wd, mode=mode,
+                     flat_params=(mode == "flat"))
+    assert exact["x"] and exact["e"], exact
+
+
+def test_every_wrap_position_small(dev):
+    """Force each start of a small problem in turn (all wrap positions)."""
+    base = wl.tiny()
+    w = wl.shrunk(base, d=37, n_tensors=3, W=3, R=5, T=37, pool=4)
+
+    exact = run_case(dev, w, forced=lambda t: t)
+    assert all(exact.values()), exact
+
+
+def _plant_specials(pool, x0):
+    g = pool[0]
+    g[0, 0:8] = [np.nan, np.inf, -np.inf, -0.0, 1e-45, -1e-45, 3e-39, 1e38]
+    g[1, 100:104] = [-0.0, -0.0, 1e-42, -1e-42]
+    pool[1][0, 5] = np.float32(1e-40)
+
+
+def test_special_values_and_denormals(dev):
+    """NaN, infinities, signed zeros and denormal gradients: the block must still
+    be the literal +0 and denormals must not be flushed."""
+    base = wl.tiny()
+    w = wl.shrunk(base, d=5000, n_tensors=2, W=2, R=4, T=4, pool=2)
+    forced = lambda t: {0: 0, 1: 4990}.get(t)   # the planted values sit inside these blocks
+    # run_case compares with the tolerance rule, which requires identical NaN and
+    # infinity patterns; NaN payload bits are not compared
+    run_case(dev, w, special=_plant_specials, momentum=0.0, weight_decay=0.0, forced=forced)
+    run_case(dev, w, special=_plant_specials, forced=forced)
+
+
+def test_set_seed_lr_step_and_resume(dev):
+    """Seed, learning-rate and step-counter changes mid-run, and a resume from a
+    checkpoint of (x, e, m, seed, t, eta) in a fresh context, follow the oracle."""
+    binding = _binding()
+    base = wl.resnet56_shaped()
+    w = wl.shrunk(base, d=9001, n_tensors=4, W=3, T=12, pool=4)
+    d, W = w.d, w.W
+    ld = wl.padded_ld(d)
+    x0 = wl.initial_params(w)
+    pool = wl.gradient_pool(w, ld=ld, threads=1)
+    gdev = [torch.from_numpy(g).to(dev) for g in pool]
+    ora = DefOracle(x0, W, w.R, w.lr, w.momentum, 0.0, w.seed)
+    x_dev = torch.from_numpy(x0).to(dev)
+    stream = torch.cuda.current_stream().cuda_stream
+    ctx = binding.DefContext(d, W, w.R, w.lr, w.momentum, 0.0, w.seed, params=x_dev, stream=stream)
+    for t in range(6):
+        if t == 2:
+            ctx.set_lr(0.01); ora.set_lr(0.01)
+        if t == 4:
+            ctx.set_seed(777); ora.set_seed(777)
+        ctx.step(gdev[t % 4], ld)
+        assert ctx.last_block()[0] == ora.step(pool[t % 4][:, :d])
+    torch.cuda.synchronize()
+    e, m, lds = fetch_state(ctx, W, d)
+    x_ck = x_dev.clone()
+    ctx.destroy()
+    # fresh context, restore, continue
+    x2 = x_ck.clone()
+    ctx2 = binding.DefContext(d, W, w.R, 0.01, w.momentum, 0.0, 777, params=x2, stream=stream)
+    e_view, m_view, _ = ctx2.state_tensors()
+    assert e_view.shape[1] == lds
+    e_view.copy_(torch.from_numpy(e).to(dev))
+    m_view.copy_(torch.from_numpy(m).to(dev))
+    ctx2.set_step(6)
+    for t in range(6, 12):
+        ctx2.step(gdev[t % 4], ld)
+        assert ctx2.last_block()[0] == ora.step(pool[t % 4][:, :d])
+    torch.cuda.synchronize()
+    e2, m2, _ = fetch_state(ctx2, W, d)
+    ctx2.destroy()
+    assert bit_equal(x2.cpu().numpy(), ora.x)
+    assert bit_equal(e2[:, :d], ora.e) and bit_equal(m2[:, :d], ora.m)
+
+
+def test_invalid_arguments_change_nothing(dev):
+    binding = _binding()
+    d, W = 1000, 2
+    x = torch.zeros(d, device=dev)
+    g = torch.ones(W, 1024, device=dev)
+    stream = torch.cuda.current_stream().cuda_stream
+    ctx = binding.DefContext(d, W, 4, 0.1, 0.9, 0.0, 1, params=x, stream=stream)
+    for call in (lambda: ctx.step(None, 1024), lambda: ctx.step(g, 999),
+                 lambda: ctx.step(g.data_ptr() + 2, 1024), lambda: ctx.force_next_start(d),
+                 lambda: ctx.output(None), lambda: ctx.last_block()):
+        with pytest.raises(binding.DefError) as ei:
+            call()
+        assert ei.value.status == binding.DEF_EINVAL
+    assert ctx.get_step() == 0
+    ctx.step(g, 1024)
+    torch.cuda.synchronize()
+    assert ctx.get_step() == 1
+    ctx.destroy()
