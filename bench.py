@@ -36,7 +36,7 @@ HBM_PEAK_GBS = 8000.0   # MI355X HBM3E peak, GB/s
 # counters are taken again.
 MEASURED_TRAFFIC = {
     ("resnet50_shaped",
-     "def_stream_vec4_kernel<mu=1,wd=1,threads=64,quads=1,nt=1,order=blocked:16384>"): 8306161344,
+     "def_stream_vec4_kernel<mu=1,wd=1,threads=64,quads=1,nt=1,order=blocked:16384,lds=10240>"): 8306331284,
 }
 
 
@@ -95,6 +95,9 @@ def main() -> int:
     ap.add_argument("--variant", default=None, choices=[None, "def", "def_a"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-budget", type=float, default=15.0)
+    ap.add_argument("--elementwise", action="store_true",
+                    help="offset the gradient buffers by one float so that the element-wise "
+                         "(any-alignment) kernel runs instead of the vectorised one")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="N",
                     help="first run N plain device-to-device copies of a 1 GiB tensor (a kernel of "
                          "known traffic, 2^30 bytes read and 2^30 written per launch, against which "
@@ -130,6 +133,13 @@ def main() -> int:
     ld = wl.padded_ld(w.d)
     x = torch.from_numpy(wl.initial_params(w)).cuda()
     pool = wl.device_gradient_pool(w, ld)
+    if args.elementwise:
+        shifted = []
+        for g in pool:
+            buf = torch.empty(g.numel() + 4, dtype=torch.float32, device="cuda")
+            buf[1:1 + g.numel()].copy_(g.view(-1))
+            shifted.append(buf[1:1 + g.numel()].view(w.W, ld))
+        pool = shifted
     stream = torch.cuda.current_stream().cuda_stream
     ctx = binding.DefContext(w.d, w.W, w.R, w.lr, w.momentum, w.weight_decay, w.seed, params=x,
                              tensor_offsets=w.tensor_offsets(), stream=stream)

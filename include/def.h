@@ -171,7 +171,7 @@ int def_last_path(const def_ctx *ctx, int *vectorised);
 
 /*
  * Name and launch shape of the streaming kernel the last step ran, e.g.
- * "def_stream_vec4_kernel<mu=1,wd=1,threads=64,quads=1,nt=1,order=blocked:16384>".
+ * "def_stream_vec4_kernel<mu=1,wd=1,threads=64,quads=1,nt=1,order=blocked:16384,lds=10240>".
  * For profiles and benchmarks that must say exactly which kernel they measured.
  * The string is owned by the context and valid until the next step or def_destroy;
  * NULL if no step has run.

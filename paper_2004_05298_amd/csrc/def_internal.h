@@ -29,6 +29,13 @@ constexpr uint32_t DEF_VEC_QUADS = 1;       // float4 groups per thread
 // workers pass over it.  Measured (d = 25.6 M, W = 16, random data): 8192 -> 78.4 %,
 // 16384 -> 79.6 %, 32768 -> 75 % of the HBM peak (the piece no longer fits in L2).
 constexpr uint32_t DEF_SUPER_TILES = 16384;
+// Dynamic LDS reserved per one-wave workgroup of the vectorised kernel.  The kernel
+// does not touch it: with 160 KiB of LDS per compute unit the reservation caps
+// residency at 16 workgroups (4 waves per SIMD).  Fewer waves in flight keep the
+// window of addresses being read and written narrower, which the memory system
+// rewards: uncapped (32 per CU) 78-79 %, 20 per CU 80.4 %, 16 per CU 81 %,
+// 13 per CU 75 % of the HBM peak (same workload, random data).
+constexpr uint32_t DEF_VEC_LDS_RESERVE = 10240;
 
 // Everything one step needs on the device.
 struct DefStepArgs {

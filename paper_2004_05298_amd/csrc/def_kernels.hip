@@ -45,6 +45,20 @@ __device__ __forceinline__ void store4(float *p, v4f v)
     else *reinterpret_cast<v4f *>(p) = v;
 }
 
+template <bool NT>
+__device__ __forceinline__ float load1(const float *p)
+{
+    if constexpr (NT) return __builtin_nontemporal_load(p);
+    else return *p;
+}
+
+template <bool NT>
+__device__ __forceinline__ void store1(float *p, float v)
+{
+    if constexpr (NT) __builtin_nontemporal_store(v, p);
+    else *p = v;
+}
+
 // The compensated value p_{k,t}[i]; updates m in place when momentum is on.
 template <bool HAS_MU, bool HAS_WD>
 __device__ __forceinline__ float compensated(float g, float &m, float e, float x,
@@ -204,12 +218,13 @@ __global__ __launch_bounds__(THREADS) void def_stream_vec4_kernel(DefStepArgs a,
 // gradient / parameter pointers; the host cuts the flat index range into chunks
 // that never cross a tensor boundary.
 // ---------------------------------------------------------------------------
-template <bool HAS_MU, bool HAS_WD>
-__global__ __launch_bounds__(DEF_THREADS) void def_stream_elem_kernel(DefStepArgs a, uint64_t total)
+template <bool HAS_MU, bool HAS_WD, int THREADS, int PER, bool NT, int MAP>
+__global__ __launch_bounds__(THREADS) void def_stream_elem_kernel(DefStepArgs a, uint64_t total,
+                                                                  uint32_t super)
 {
     uint32_t k;
     uint64_t chunk;
-    if (!decode_item<MAP_XCD_K>(total, a.n_chunks, a.W, 0, k, chunk)) return;
+    if (!decode_item<MAP>(total, a.n_chunks, a.W, super, k, chunk)) return;
     const DefChunk ch = a.chunks[chunk];
     const uint64_t local = ch.start - a.off[ch.tensor];       // offset inside the tensor
 
@@ -221,22 +236,22 @@ __global__ __launch_bounds__(DEF_THREADS) void def_stream_elem_kernel(DefStepArg
     float *__restrict__ m = HAS_MU ? a.m + (uint64_t)k * a.ld + ch.start : nullptr;
     float *__restrict__ msg = a.msg + (uint64_t)k * a.ldmsg;
 
-    constexpr int PER = DEF_ELEM_CHUNK / DEF_THREADS;
+    // the host cuts chunks of at most THREADS*PER indices
     float gv[PER], mv[PER], ev[PER], xv[PER];
 #pragma unroll
     for (int u = 0; u < PER; ++u) {
-        const uint32_t o = threadIdx.x + u * DEF_THREADS;
+        const uint32_t o = threadIdx.x + u * THREADS;
         gv[u] = 0.0f; mv[u] = 0.0f; ev[u] = 0.0f; xv[u] = 0.0f;
         if (o < ch.len) {
-            gv[u] = g[o];
-            if constexpr (HAS_MU) mv[u] = m[o];
-            ev[u] = e[o];
+            gv[u] = load1<NT>(g + o);
+            if constexpr (HAS_MU) mv[u] = load1<NT>(m + o);
+            ev[u] = load1<NT>(e + o);
             if constexpr (HAS_WD) xv[u] = x[o];
         }
     }
 #pragma unroll
     for (int u = 0; u < PER; ++u) {
-        const uint32_t o = threadIdx.x + u * DEF_THREADS;
+        const uint32_t o = threadIdx.x + u * THREADS;
         if (o >= ch.len) continue;
         float mc = mv[u];
         const float p = compensated<HAS_MU, HAS_WD>(gv[u], mc, ev[u], xv[u], a.lr, a.mu, a.wd);
@@ -247,8 +262,8 @@ __global__ __launch_bounds__(DEF_THREADS) void def_stream_elem_kernel(DefStepArg
             msg[j] = p;
             en = 0.0f;
         }
-        if constexpr (HAS_MU) m[o] = mc;
-        e[o] = en;
+        if constexpr (HAS_MU) store1<NT>(m + o, mc);
+        store1<NT>(e + o, en);
     }
 }
 
@@ -339,11 +354,11 @@ void def_describe_stream_kernel(const DefStepArgs &a, bool vec, char *out, size_
         char order[32];
         if (wd) std::snprintf(order, sizeof order, "blocked:%u", DEF_SUPER_TILES);
         else std::snprintf(order, sizeof order, "linear");
-        std::snprintf(out, cap, "def_stream_vec4_kernel<mu=%d,wd=%d,threads=%u,quads=%u,nt=1,order=%s>",
-                      mu, wd, DEF_VEC_THREADS, DEF_VEC_QUADS, order);
+        std::snprintf(out, cap, "def_stream_vec4_kernel<mu=%d,wd=%d,threads=%u,quads=%u,nt=1,order=%s,lds=%u>",
+                      mu, wd, DEF_VEC_THREADS, DEF_VEC_QUADS, order, DEF_VEC_LDS_RESERVE);
     } else {
-        std::snprintf(out, cap, "def_stream_elem_kernel<mu=%d,wd=%d,threads=%u,chunk=%u>", mu, wd,
-                      DEF_THREADS, DEF_ELEM_CHUNK);
+        std::snprintf(out, cap, "def_stream_elem_kernel<mu=%d,wd=%d,threads=%u,chunk=%u,nt=1,order=%s>", mu, wd,
+                      DEF_THREADS, DEF_ELEM_CHUNK, wd ? "blocked" : "linear");
     }
 }
 
@@ -364,26 +379,30 @@ hipError_t def_launch_stream_vec4(const DefStepArgs &a, hipStream_t st)
     // blocked order lets all W workers pass over a piece of x while it sits in L2,
     // so x is fetched from HBM once per step instead of W times.
     if (mu && wd)
-        def_stream_vec4_kernel<true, true, T, U, NL, NS, MAP_BLOCKED><<<grid, block, 0, st>>>(a, tiles, total, DEF_SUPER_TILES);
+        def_stream_vec4_kernel<true, true, T, U, NL, NS, MAP_BLOCKED><<<grid, block, DEF_VEC_LDS_RESERVE, st>>>(a, tiles, total, DEF_SUPER_TILES);
     else if (mu)
-        def_stream_vec4_kernel<true, false, T, U, NL, NS, MAP_LINEAR_T><<<grid, block, 0, st>>>(a, tiles, total, 0);
+        def_stream_vec4_kernel<true, false, T, U, NL, NS, MAP_LINEAR_T><<<grid, block, DEF_VEC_LDS_RESERVE, st>>>(a, tiles, total, 0);
     else if (wd)
-        def_stream_vec4_kernel<false, true, T, U, NL, NS, MAP_BLOCKED><<<grid, block, 0, st>>>(a, tiles, total, DEF_SUPER_TILES);
+        def_stream_vec4_kernel<false, true, T, U, NL, NS, MAP_BLOCKED><<<grid, block, DEF_VEC_LDS_RESERVE, st>>>(a, tiles, total, DEF_SUPER_TILES);
     else
-        def_stream_vec4_kernel<false, false, T, U, NL, NS, MAP_LINEAR_T><<<grid, block, 0, st>>>(a, tiles, total, 0);
+        def_stream_vec4_kernel<false, false, T, U, NL, NS, MAP_LINEAR_T><<<grid, block, DEF_VEC_LDS_RESERVE, st>>>(a, tiles, total, 0);
     return hipGetLastError();
 }
 
 hipError_t def_launch_stream_elem(const DefStepArgs &a, hipStream_t st)
 {
+    constexpr int T = DEF_THREADS, PER = DEF_ELEM_CHUNK / DEF_THREADS;
+    static_assert(T * PER >= (int)DEF_ELEM_CHUNK, "a workgroup must cover a whole chunk");
+    // super-tile of the blocked order, in chunks: the same 16 MiB of x as the vectorised kernel
+    constexpr uint32_t SUPER = DEF_SUPER_TILES * DEF_VEC_THREADS * DEF_VEC_QUADS * 4 / DEF_ELEM_CHUNK;
     const uint64_t total = (uint64_t)a.n_chunks * a.W;
     if (total > 0x7fffffffull - 8) return hipErrorInvalidConfiguration;
-    const dim3 grid(grid_for(total)), block(DEF_THREADS);
+    const dim3 grid(grid_for(total)), block(T);
     const bool mu = a.mu != 0.0f, wd = a.wd != 0.0f;
-    if (mu && wd) def_stream_elem_kernel<true, true><<<grid, block, 0, st>>>(a, total);
-    else if (mu) def_stream_elem_kernel<true, false><<<grid, block, 0, st>>>(a, total);
-    else if (wd) def_stream_elem_kernel<false, true><<<grid, block, 0, st>>>(a, total);
-    else def_stream_elem_kernel<false, false><<<grid, block, 0, st>>>(a, total);
+    if (mu && wd) def_stream_elem_kernel<true, true, T, PER, true, MAP_BLOCKED><<<grid, block, 0, st>>>(a, total, SUPER);
+    else if (mu) def_stream_elem_kernel<true, false, T, PER, true, MAP_LINEAR_T><<<grid, block, 0, st>>>(a, total, 0);
+    else if (wd) def_stream_elem_kernel<false, true, T, PER, true, MAP_BLOCKED><<<grid, block, 0, st>>>(a, total, SUPER);
+    else def_stream_elem_kernel<false, false, T, PER, true, MAP_LINEAR_T><<<grid, block, 0, st>>>(a, total, 0);
     return hipGetLastError();
 }
 
