@@ -43,6 +43,8 @@ def lib():
         L.def_oracle_step_f32.restype = None
         L.def_oracle_y_f32.argtypes = [ctypes.c_int64, ctypes.c_int32, f32p, f32p, f32p]
         L.def_oracle_y_f32.restype = None
+        L.def_oracle_detach_f32.argtypes = [ctypes.c_int64, ctypes.c_int32, ctypes.c_float, f32p, f32p, f32p]
+        L.def_oracle_detach_f32.restype = None
         L.def_oracle_threads.restype = ctypes.c_int
         L.def_oracle_set_threads.argtypes = [ctypes.c_int]
         _lib = L
@@ -109,6 +111,12 @@ class DefOracleC:
     def y(self) -> np.ndarray:
         out = np.empty_like(self.x)
         self._lib.def_oracle_y_f32(self.x.shape[0], self.W, _p(self.x), _p(self.e), _p(out))
+        return out
+
+    def detached_points(self, lam: float) -> np.ndarray:
+        out = np.empty_like(self.e)
+        self._lib.def_oracle_detach_f32(self.x.shape[0], self.W, np.float32(lam), _p(self.x), _p(self.e),
+                                        _p(out))
         return out
 
     def compact_block(self) -> np.ndarray:

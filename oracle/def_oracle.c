@@ -116,6 +116,21 @@ void def_oracle_step_f32(int64_t n, int64_t d, int32_t W, int64_t B, int64_t s,
     }
 }
 
+/* w_k = x - lambda*e_k for every worker (Algorithm 1, "detach" line); w is [W][n]. */
+void def_oracle_detach_f32(int64_t n, int32_t W, float lambda, const float *x, const float *e,
+                           float *w)
+{
+    int32_t k;
+    for (k = 0; k < W; ++k) {
+        int64_t c;
+#pragma omp parallel for schedule(static)
+        for (c = 0; c < n; ++c) {
+            float scaled = lambda * e[(size_t)k * (size_t)n + (size_t)c];
+            w[(size_t)k * (size_t)n + (size_t)c] = x[c] - scaled;
+        }
+    }
+}
+
 /* y = x - (sum_k e_k) / W, k ascending. */
 void def_oracle_y_f32(int64_t n, int32_t W, const float *x, const float *e, float *y)
 {

@@ -13,6 +13,8 @@ What it follows (arXiv 2004.05298):
   with m_{k,0} = 0.
 * Algorithm 1 "Output" / Sec. 3.2 Eq. "y update":  y = x - (1/K) sum_k e_k for
   DEF, x itself for DEF-A.  DEF and DEF-A run the same iteration.
+* Algorithm 1, "detach" line:  worker k evaluates its next gradient at
+  x - lambda*e_k  (`detached_points`).
 * Sec. 1 (RBGS): the compressor C keeps ONE contiguous block of the flattened
   vector whose start index is sampled uniformly; all workers share the seed and
   therefore the block.
@@ -154,6 +156,16 @@ class DefOracle:
         for k in range(self.W):
             acc = acc + self.e[k]
         return self.x - acc / self.dtype.type(self.W)
+
+    def detached_points(self, lam: float) -> np.ndarray:
+        """The points w_k = x - lambda*e_k at which worker k evaluates its next
+        gradient (Algorithm 1, "detach" line), one row per worker.  lambda*e_k
+        and the subtraction round separately."""
+        lam = self.dtype.type(lam)
+        out = np.empty_like(self.e)
+        for k in range(self.W):
+            out[k] = self.x - lam * self.e[k]
+        return out
 
     def compact_block(self) -> np.ndarray:
         """The averaged block of the last step as the B-vector that would be

@@ -34,6 +34,10 @@ def _pin_calls():
     calls.append(lambda: pins.test_y_follows_uncompressed_momentum_path("np64", 1e-12, 61, 3, 7))
     calls.append(lambda: pins.test_single_worker_lemma_x_chases_sgd_path())
     calls.append(lambda: pins.test_block_length_is_the_ceiling())
+    for kind in ("np32", "np64"):
+        calls.append(lambda k=kind: pins.test_detached_points_special_cases(k))
+    calls.append(lambda: pins.test_detached_points_distance_identity())
+    calls.append(lambda: pins.test_closed_loop_single_worker_follows_gradient_descent("np64", 1e-12))
     return calls
 
 
@@ -91,6 +95,10 @@ MUTANTS = [
     ("y sign", "return self.x - acc / self.dtype.type(self.W)", "return self.x + acc / self.dtype.type(self.W)"),
     ("y not averaged", "return self.x - acc / self.dtype.type(self.W)", "return self.x - acc"),
     ("step counter stuck", "self.t += 1", "self.t += 0"),
+    ("detach sign", "out[k] = self.x - lam * self.e[k]", "out[k] = self.x + lam * self.e[k]"),
+    ("detach ignores lambda", "out[k] = self.x - lam * self.e[k]", "out[k] = self.x - self.e[k]"),
+    ("detach uses momentum", "out[k] = self.x - lam * self.e[k]", "out[k] = self.x - lam * self.m[k]"),
+    ("detach uses worker 0", "out[k] = self.x - lam * self.e[k]", "out[k] = self.x - lam * self.e[0]"),
 ]
 
 PHILOX_MUTANTS = [

@@ -308,6 +308,75 @@ def test_scaling_compressor_gives_iterate_averaging():
 
 
 # --------------------------------------------------------------------------- #
+# Detached evaluation points (Algorithm 1, "detach" line; Sec. 3.2 items (1)-(3);
+# Appendix A, first display).
+# --------------------------------------------------------------------------- #
+@pytest.mark.parametrize("kind", KINDS)
+def test_detached_points_special_cases(kind):
+    """lambda = 0 is plain error feedback (gradient at x); K = 1 with lambda = 1
+    evaluates at y = x - e, the SGD path (Sec. 3.2, text after Eq. "y update")."""
+    d, R, T = 41, 6, 9
+    rng = np.random.default_rng(91)
+    many = make(kind, rng.standard_normal(d), 3, R, 0.2, 0.9, 0.0, seed=12)
+    one = make(kind, rng.standard_normal(d), 1, R, 0.2, 0.9, 0.0, seed=12)
+    for t in range(T):
+        many.step(rng.standard_normal((3, d)).astype(np.float32))
+        one.step(rng.standard_normal((1, d)).astype(np.float32))
+    w0 = np.asarray(many.detached_points(0.0))
+    assert w0.shape == (3, d)
+    for k in range(3):
+        assert np.array_equal(w0[k], np.asarray(many.x))
+    assert np.array_equal(np.asarray(one.detached_points(1.0))[0], np.asarray(one.y()))
+    assert np.asarray(many.e).any()
+
+
+def test_detached_points_distance_identity():
+    """(1/K) sum_k ||w_k - y||^2 = (1/K) sum_k ||e_t - lambda e_k||^2
+    = lambda^2 * mean_k||e_k||^2 - 2 lambda ||e_t||^2 + ||e_t||^2  with e_t the mean
+    error (Sec. 3.2, Eq. "min d"; Appendix A, first display), and lambda*(t) =
+    ||e_t||^2 / mean_k||e_k||^2 minimises it."""
+    d, W, R, T = 60, 5, 7, 14
+    rng = np.random.default_rng(92)
+    o = make("np64", rng.standard_normal(d), W, R, 0.1, 0.9, 0.0, seed=3)
+    for t in range(T):
+        o.step(rng.standard_normal((W, d)))
+    e_bar = o.e.mean(axis=0)
+    mean_sq = float((o.e ** 2).sum(axis=1).mean())
+    bar_sq = float((e_bar ** 2).sum())
+    assert mean_sq > 0 and bar_sq > 0
+
+    def dist(lam):
+        return float(((o.detached_points(lam) - o.y()[None, :]) ** 2).sum(axis=1).mean())
+
+    for lam in (0.0, 0.3, 0.7, 1.0):
+        assert dist(lam) == pytest.approx(lam * lam * mean_sq - 2 * lam * bar_sq + bar_sq, rel=1e-11)
+    lam_star = bar_sq / mean_sq
+    assert 0.0 < lam_star < 1.0
+    assert dist(lam_star) <= min(dist(lam_star - 1e-3), dist(lam_star + 1e-3))
+    assert dist(lam_star) == pytest.approx(bar_sq * (mean_sq - bar_sq) / mean_sq, rel=1e-10)
+
+
+@pytest.mark.parametrize("kind,tol", [("np64", 1e-12), ("np32", 2e-5), ("c32", 2e-5)])
+def test_closed_loop_single_worker_follows_gradient_descent(kind, tol):
+    """K = 1, lambda = 1 on f(theta) = 0.5*||theta - c||^2 with the gradient taken at
+    the detached point: y_t must be exact gradient descent whatever the compressor
+    drops, y_t = c + (1 - eta)^t (y_0 - c)  (Sec. 3.2: for K = 1, lambda = 1 the
+    sequence {y_t} is the SGD solution path)."""
+    d, R, T, lr = 30, 5, 25, 0.2
+    rng = np.random.default_rng(93)
+    c = rng.standard_normal(d)
+    y0 = rng.standard_normal(d)
+    o = make(kind, y0, 1, R, lr, 0.0, 0.0, seed=21)
+    y0s = np.asarray(o.x, dtype=np.float64).copy()
+    for t in range(T):
+        w = np.asarray(o.detached_points(1.0), dtype=np.float64)
+        o.step((w - c[None, :]).astype(np.float32 if kind != "np64" else np.float64))
+        ref = c + (1 - lr) ** (t + 1) * (y0s - c)
+        assert np.allclose(np.asarray(o.y(), dtype=np.float64), ref, rtol=tol, atol=tol), t
+    assert np.abs(np.asarray(o.e)).max() > 1e-3      # the compressor did drop something
+
+
+# --------------------------------------------------------------------------- #
 # Integer closed form (follows from Algorithm 1 with g = 1, eta = 1).
 # --------------------------------------------------------------------------- #
 @pytest.mark.parametrize("kind", KINDS)
