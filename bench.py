@@ -36,11 +36,11 @@ HBM_PEAK_GBS = 8000.0   # MI355X HBM3E peak, GB/s
 # counters are taken again.
 MEASURED_TRAFFIC = {
     ("resnet50_shaped",
-     "def_stream_vec4_kernel<mu=1,wd=1,threads=64,quads=1,nt=1,order=blocked:16384,lds=10240>"): 8306331284,
+     "def_stream_vec4_kernel<mu=1,wd=1,detach=0,threads=64,quads=1,nt=1,order=blocked:16384,lds=10240>"): 8305018135,
 }
 
 
-def algorithmic_bytes(w, y_out=False):
+def algorithmic_bytes(w, y_out=False, detach=False):
     """Bytes the method itself must move per step (fp32): per (worker, index) one
     gradient read, error memory read+write and, with momentum, momentum read+write;
     plus x: read once everywhere when weight decay needs it, else read on the
@@ -55,6 +55,11 @@ def algorithmic_bytes(w, y_out=False):
     extra = 0
     if y_out:
         extra = 4 * w.d + (0 if w.weight_decay != 0 else 4 * w.d)
+    if detach:
+        # w_k = x - lambda*e_k: one more write per (worker, index); x read once everywhere
+        stream += 4 * w.W * w.d
+        if w.weight_decay == 0:
+            stream_x, block = 4 * w.d, 4 * w.B
     return dict(step=stream + stream_x + block + extra, stream_kernel=stream + stream_x)
 
 
@@ -95,6 +100,9 @@ def main() -> int:
     ap.add_argument("--variant", default=None, choices=[None, "def", "def_a"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-budget", type=float, default=15.0)
+    ap.add_argument("--detach", type=float, default=None, metavar="LAMBDA",
+                    help="also write the detached evaluation points w_k = x - LAMBDA*e_k in the "
+                         "same pass (24 instead of 20 bytes per worker and index)")
     ap.add_argument("--elementwise", action="store_true",
                     help="offset the gradient buffers by one float so that the element-wise "
                          "(any-alignment) kernel runs instead of the vectorised one")
@@ -144,6 +152,11 @@ def main() -> int:
     ctx = binding.DefContext(w.d, w.W, w.R, w.lr, w.momentum, w.weight_decay, w.seed, params=x,
                              tensor_offsets=w.tensor_offsets(), stream=stream)
 
+    w_out = None
+    if args.detach is not None:
+        w_out = torch.empty((w.W, ld), dtype=torch.float32, device="cuda")
+        ctx.set_detach(w_out, ld, args.detach)
+
     def one_step(t):
         forced = w.forced_start(t)
         if forced is not None:
@@ -171,7 +184,7 @@ def main() -> int:
     kernel_name = ctx.last_kernel()
     ctx.destroy()
 
-    ab = algorithmic_bytes(w)
+    ab = algorithmic_bytes(w, detach=args.detach is not None)
     per_step = elapsed / args.steps
     value = ab["step"] / per_step / 1e9
     k_avg_ms = sum(kernel_ms) / len(kernel_ms)
@@ -187,7 +200,7 @@ def main() -> int:
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": w.name, "d": w.d, "W": w.W, "R": w.R, "B": w.B,
                    "n_tensors": w.n_tensors, "momentum": w.momentum,
-                   "weight_decay": w.weight_decay, "lr": w.lr, "variant": variant,
+                   "weight_decay": w.weight_decay, "lr": w.lr, "variant": variant, "detach_lambda": args.detach,
                    "gradient_sets": w.pool, "path": "dwordx4" if vectorised else "dword",
                    "algorithmic_bytes_per_step": ab["step"]},
         "roofline": {"bound": "hbm", "kernel": kernel_name,

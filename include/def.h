@@ -51,7 +51,8 @@ typedef struct def_ctx def_ctx; /* opaque, owned by the library */
  */
 typedef struct def_config {
     uint64_t d;             /* number of parameters, 1 <= d < 2^40                              */
-    uint32_t W;             /* number of workers (the paper's K), >= 1                          */
+    uint32_t W;             /* number of workers (the paper's K), >= 1; W * ceil(d/256) must be
+                               below 2^31 (one workgroup per worker and 256 indices)            */
     uint32_t R;             /* compression ratio, integer, 1 <= R <= d.  The kept block has
                                B = ceil(d/R) elements (delta = B/d, Assumption 5).              */
     float lr;               /* learning rate eta                                                */
@@ -126,6 +127,25 @@ int def_a_step_tensors(def_ctx *ctx, const float *const *grad_ptrs);
  */
 int def_output(def_ctx *ctx, float *y_out);
 
+/*
+ * Detached evaluation points (Algorithm 1, "detach" line; Sec. 3.2): worker k
+ * computes its next gradient at  w_k = x - lambda * e_k,  lambda in [0, 1]
+ * (0.3 in the paper's experiments; lambda = 0 is plain error feedback).
+ *
+ * def_set_detach  from now on every step also writes, in the same pass,
+ *                 w_out[k*ldw + i] = x_{t+1}[i] - lambda * e_{k,t+1}[i]
+ *                 for all workers k and indices i.  w_out: DEVICE, [W][ldw] floats,
+ *                 ldw >= d, caller-owned, must stay valid while set; 16-byte
+ *                 alignment and ldw % 4 == 0 keep the vectorised path.
+ *                 w_out == NULL switches it off.  Before the first step the
+ *                 points are x_0 itself (e_{k,0} = 0).
+ * def_detach      writes the same quantity for the CURRENT state (after a restore,
+ *                 or with another lambda) without stepping.
+ * DEF_EINVAL for lambda outside [0, 1], ldw < d, or a misaligned pointer.
+ */
+int def_set_detach(def_ctx *ctx, float *w_out, uint64_t ldw, float lambda);
+int def_detach(def_ctx *ctx, float *w_out, uint64_t ldw, float lambda);
+
 /* Replace the seed (Sec. 1: the seed all workers share).  t keeps counting. */
 int def_set_seed(def_ctx *ctx, uint64_t seed);
 
@@ -171,7 +191,7 @@ int def_last_path(const def_ctx *ctx, int *vectorised);
 
 /*
  * Name and launch shape of the streaming kernel the last step ran, e.g.
- * "def_stream_vec4_kernel<mu=1,wd=1,threads=64,quads=1,nt=1,order=blocked:16384,lds=10240>".
+ * "def_stream_vec4_kernel<mu=1,wd=1,detach=0,threads=64,...>".
  * For profiles and benchmarks that must say exactly which kernel they measured.
  * The string is owned by the context and valid until the next step or def_destroy;
  * NULL if no step has run.

@@ -40,6 +40,8 @@ SIGNATURES = {
     "def_step_tensors": (ctypes.c_int, [_vp, ctypes.POINTER(_vp), _vp]),
     "def_a_step_tensors": (ctypes.c_int, [_vp, ctypes.POINTER(_vp)]),
     "def_output": (ctypes.c_int, [_vp, _vp]),
+    "def_set_detach": (ctypes.c_int, [_vp, _vp, _u64, _f32]),
+    "def_detach": (ctypes.c_int, [_vp, _vp, _u64, _f32]),
     "def_set_seed": (ctypes.c_int, [_vp, _u64]),
     "def_set_lr": (ctypes.c_int, [_vp, _f32]),
     "def_set_step": (ctypes.c_int, [_vp, _u64]),
@@ -202,6 +204,13 @@ class DefContext:
 
     def output(self, y_out) -> None:
         _check(self._lib.def_output(self._h, _ptr(y_out)), "def_output")
+
+    def set_detach(self, w_out, ldw: int = 0, lam: float = 0.0) -> None:
+        self._keep.append(w_out)
+        _check(self._lib.def_set_detach(self._h, _ptr(w_out), ldw, lam), "def_set_detach")
+
+    def detach(self, w_out, ldw: int, lam: float) -> None:
+        _check(self._lib.def_detach(self._h, _ptr(w_out), ldw, lam), "def_detach")
 
     # -- knobs ----------------------------------------------------------------
     def set_seed(self, seed: int) -> None:

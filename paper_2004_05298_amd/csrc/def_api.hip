@@ -78,6 +78,10 @@ struct def_ctx {
     // parameters
     float *x_flat = nullptr;
     float **d_xptrs = nullptr;
+    // detached evaluation points requested with def_set_detach
+    float *w = nullptr;
+    uint64_t ldw = 0;
+    float lam = 0;
     // gradient pointer table (tensor mode)
     const float **d_gptrs = nullptr;
     std::vector<const float *> h_gptrs;
@@ -113,6 +117,7 @@ DefStepArgs base_args(const def_ctx *c, uint64_t s)
     a.msg = c->msg; a.ldmsg = c->ldmsg; a.avg = c->avg;
     a.x_flat = c->x_flat; a.x_ptrs = c->d_xptrs; a.off = c->d_off; a.L = c->L;
     a.chunks = c->d_chunks; a.n_chunks = c->n_chunks;
+    a.w = c->w; a.ldw = c->ldw; a.lam = c->lam;
     return a;
 }
 
@@ -176,6 +181,15 @@ int def_init(def_ctx **out, const def_config *cfg)
         return DEF_EINVAL;
     }
 
+    {
+        // one workgroup per (worker, tile) resp. (worker, chunk): the grid must fit 31 bits
+        const uint64_t grid_limit = 0x7fffffffull - 8;
+        const uint64_t per_tile = DEF_VEC_THREADS * DEF_VEC_QUADS * 4;
+        const uint64_t vec_tiles = (cfg->d + per_tile - 1) / per_tile;
+        const uint64_t max_chunks = cfg->d / DEF_ELEM_CHUNK + L;   // each tensor adds at most one short chunk
+        if (vec_tiles * cfg->W > grid_limit || max_chunks * cfg->W > grid_limit) return DEF_EINVAL;
+    }
+
     def_ctx *c = new (std::nothrow) def_ctx;
     if (!c) return DEF_ENOMEM;
     c->d = cfg->d; c->W = cfg->W; c->R = cfg->R; c->L = L;
@@ -203,7 +217,6 @@ int def_init(def_ctx **out, const def_config *cfg)
         free_ctx(c);
         return DEF_ENOMEM;
     }
-    if (chunks.size() > 0x7fffffffull) { free_ctx(c); return DEF_EINVAL; }
     c->n_chunks = (uint32_t)chunks.size();
 
 #define DEF_INIT_HIP(call)                                                      \
@@ -255,9 +268,11 @@ int def_step(def_ctx *ctx, const float *grads, uint64_t ld, float *y_out)
     a.g_flat = grads;
     a.ldg = ld;
     a.g_ptrs = nullptr;
-    // x is read by the streaming pass only for weight decay
-    const bool x_ok = ctx->wd == 0.0f || (ctx->x_flat && (uintptr_t)ctx->x_flat % 16 == 0);
-    const bool vec = (uintptr_t)grads % 16 == 0 && ld % 4 == 0 && x_ok;
+    // the streaming pass reads x only for weight decay and for the detached points
+    const bool reads_x = ctx->wd != 0.0f || ctx->w;
+    const bool x_ok = !reads_x || (ctx->x_flat && (uintptr_t)ctx->x_flat % 16 == 0);
+    const bool w_ok = !ctx->w || ((uintptr_t)ctx->w % 16 == 0 && ctx->ldw % 4 == 0);
+    const bool vec = (uintptr_t)grads % 16 == 0 && ld % 4 == 0 && x_ok && w_ok;
     return run_step(ctx, a, vec, y_out);
 }
 
@@ -299,6 +314,30 @@ int def_output(def_ctx *ctx, float *y_out)
     if (!ctx || !y_out || (uintptr_t)y_out % 4 != 0) return DEF_EINVAL;
     DefStepArgs a = base_args(ctx, 0);
     DEF_HIP(def_launch_output(a, y_out, ctx->stream));
+    return DEF_OK;
+}
+
+int def_set_detach(def_ctx *ctx, float *w_out, uint64_t ldw, float lambda)
+{
+    if (!ctx) return DEF_EINVAL;
+    if (w_out) {
+        if ((uintptr_t)w_out % 4 != 0 || ldw < ctx->d || !(lambda >= 0.0f && lambda <= 1.0f))
+            return DEF_EINVAL;
+        ctx->w = w_out; ctx->ldw = ldw; ctx->lam = lambda;
+    } else {
+        ctx->w = nullptr; ctx->ldw = 0; ctx->lam = 0.0f;
+    }
+    return DEF_OK;
+}
+
+int def_detach(def_ctx *ctx, float *w_out, uint64_t ldw, float lambda)
+{
+    if (!ctx || !w_out || (uintptr_t)w_out % 4 != 0 || ldw < ctx->d ||
+        !(lambda >= 0.0f && lambda <= 1.0f))
+        return DEF_EINVAL;
+    DefStepArgs a = base_args(ctx, 0);
+    a.w = w_out; a.ldw = ldw; a.lam = lambda;
+    DEF_HIP(def_launch_detach(a, ctx->stream));
     return DEF_OK;
 }
 

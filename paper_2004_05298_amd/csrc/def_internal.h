@@ -64,12 +64,17 @@ struct DefStepArgs {
     // element-wise kernel work list
     const DefChunk *chunks;
     uint32_t n_chunks;
+    // detached evaluation points w_k = x - lambda*e_k (nullptr: not requested)
+    float *w;                  // [W][ldw]
+    uint64_t ldw;
+    float lam;
 };
 
 // Text describing the instantiation def_launch_stream_vec4 / _elem picks for these arguments.
 void def_describe_stream_kernel(const DefStepArgs &a, bool vec, char *out, size_t cap);
 // Fused momentum + error feedback + compress + residual pass, dwordx4 accesses.
-// Needs: g_flat 16-byte aligned, ldg % 4 == 0, x_flat (if wd != 0) 16-byte aligned.
+// Needs: g_flat 16-byte aligned, ldg % 4 == 0; x_flat 16-byte aligned if x is read (wd != 0 or
+// w requested); w 16-byte aligned with ldw % 4 == 0.
 hipError_t def_launch_stream_vec4(const DefStepArgs &a, hipStream_t st);
 // Same pass, one dword per access, any alignment, flat or per-tensor pointers.
 hipError_t def_launch_stream_elem(const DefStepArgs &a, hipStream_t st);
@@ -77,3 +82,5 @@ hipError_t def_launch_stream_elem(const DefStepArgs &a, hipStream_t st);
 hipError_t def_launch_average_update(const DefStepArgs &a, hipStream_t st);
 // y = x - mean_k e_k.
 hipError_t def_launch_output(const DefStepArgs &a, float *y, hipStream_t st);
+// w_k = x - lambda*e_k for the current state (a.w, a.ldw, a.lam).
+hipError_t def_launch_detach(const DefStepArgs &a, hipStream_t st);

@@ -8,6 +8,8 @@
 //     msg_k[(i - s) mod d] = p  for i in block     (C(p_k), compact)
 // then  cbar[j] = (1/W) sum_k msg_k[j]             (Algorithm 1, all-reduce line)
 //       x[(s+j) mod d] -= cbar[j]                  (Algorithm 1, update line)
+// and, when asked for, the points at which the next gradients are to be evaluated,
+//       w_k[i] = x_{t+1}[i] - lambda*e_{k,t+1}[i]  (Algorithm 1, "detach" line).
 // The block {(s+j) mod d : j < B} is the RBGS compressor of Sec. 1.
 //
 // Nothing here is a contraction: the step is a streaming pass of five 4-byte
@@ -127,10 +129,11 @@ __device__ __forceinline__ bool decode_item(uint64_t total, uint64_t tiles, uint
 // THREADS*U float4 groups; thread t owns groups t, t+THREADS, ... so that each wave
 // instruction touches 1 KiB of consecutive memory.
 // ---------------------------------------------------------------------------
-template <bool HAS_MU, bool HAS_WD, int THREADS, int U, bool NT_LD, bool NT_ST, int MAP>
+template <bool HAS_MU, bool HAS_WD, bool HAS_DT, int THREADS, int U, bool NT_LD, bool NT_ST, int MAP>
 __global__ __launch_bounds__(THREADS) void def_stream_vec4_kernel(DefStepArgs a, uint64_t tiles,
                                                                   uint64_t total, uint32_t super)
 {
+    constexpr bool HAS_X = HAS_WD || HAS_DT;             // x is read for weight decay and for w
     uint32_t k;
     uint64_t tile;
     if (!decode_item<MAP>(total, tiles, a.W, super, k, tile)) return;
@@ -140,6 +143,7 @@ __global__ __launch_bounds__(THREADS) void def_stream_vec4_kernel(DefStepArgs a,
     float *__restrict__ m = HAS_MU ? a.m + (uint64_t)k * a.ld : nullptr;
     float *__restrict__ msg = a.msg + (uint64_t)k * a.ldmsg;
     const float *__restrict__ x = a.x_flat;
+    float *__restrict__ w = HAS_DT ? a.w + (uint64_t)k * a.ldw : nullptr;
 
     constexpr uint64_t STRIDE = THREADS * 4;             // elements between a thread's groups
     const uint64_t i_first = (tile * (uint64_t)(THREADS * U) + threadIdx.x) * 4;
@@ -154,7 +158,7 @@ __global__ __launch_bounds__(THREADS) void def_stream_vec4_kernel(DefStepArgs a,
             gv[u] = load4<NT_LD>(g + i);
             if constexpr (HAS_MU) mv[u] = load4<NT_LD>(m + i);
             ev[u] = load4<NT_LD>(e + i);
-            if constexpr (HAS_WD) xv[u] = load4<false>(x + i);
+            if constexpr (HAS_X) xv[u] = load4<false>(x + i);
         }
     } else {
         // last tile of the row: a group may be cut by d or lie beyond it.  The
@@ -166,13 +170,13 @@ __global__ __launch_bounds__(THREADS) void def_stream_vec4_kernel(DefStepArgs a,
             gv[u] = (v4f)(0.0f); mv[u] = (v4f)(0.0f); ev[u] = (v4f)(0.0f); xv[u] = (v4f)(0.0f);
             if (i + 4 <= a.d) {
                 gv[u] = load4<NT_LD>(g + i);
-                if constexpr (HAS_WD) xv[u] = load4<false>(x + i);
+                if constexpr (HAS_X) xv[u] = load4<false>(x + i);
             } else if (i < a.d) {
 #pragma unroll
                 for (int c = 0; c < 4; ++c)
                     if (i + c < a.d) {
                         gv[u][c] = g[i + c];
-                        if constexpr (HAS_WD) xv[u][c] = x[i + c];
+                        if constexpr (HAS_X) xv[u][c] = x[i + c];
                     }
             }
             if (i < a.d) {
@@ -210,6 +214,24 @@ __global__ __launch_bounds__(THREADS) void def_stream_vec4_kernel(DefStepArgs a,
         }
         if constexpr (HAS_MU) store4<NT_ST>(m + i, mv[u]);
         store4<NT_ST>(e + i, en);
+        if constexpr (HAS_DT) {
+            // w = x - lambda*e_new.  Off the block x does not change in this step.  On
+            // the block this writes x_t - lambda*0; the averaging kernel, which runs
+            // after this one, replaces those entries by x_{t+1}.
+            v4f wv;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const float scaled = a.lam * en[c];
+                wv[c] = xv[u][c] - scaled;
+            }
+            if (i + 4 <= a.d) {
+                store4<NT_ST>(w + i, wv);
+            } else {
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+                    if (i + c < a.d) w[i + c] = wv[c];
+            }
+        }
     }
 }
 
@@ -218,10 +240,11 @@ __global__ __launch_bounds__(THREADS) void def_stream_vec4_kernel(DefStepArgs a,
 // gradient / parameter pointers; the host cuts the flat index range into chunks
 // that never cross a tensor boundary.
 // ---------------------------------------------------------------------------
-template <bool HAS_MU, bool HAS_WD, int THREADS, int PER, bool NT, int MAP>
+template <bool HAS_MU, bool HAS_WD, bool HAS_DT, int THREADS, int PER, bool NT, int MAP>
 __global__ __launch_bounds__(THREADS) void def_stream_elem_kernel(DefStepArgs a, uint64_t total,
                                                                   uint32_t super)
 {
+    constexpr bool HAS_X = HAS_WD || HAS_DT;
     uint32_t k;
     uint64_t chunk;
     if (!decode_item<MAP>(total, a.n_chunks, a.W, super, k, chunk)) return;
@@ -231,7 +254,8 @@ __global__ __launch_bounds__(THREADS) void def_stream_elem_kernel(DefStepArgs a,
     const float *__restrict__ g = a.g_ptrs ? a.g_ptrs[(uint64_t)k * a.L + ch.tensor] + local
                                            : a.g_flat + (uint64_t)k * a.ldg + ch.start;
     const float *__restrict__ x = nullptr;
-    if constexpr (HAS_WD) x = a.x_ptrs ? a.x_ptrs[ch.tensor] + local : a.x_flat + ch.start;
+    if constexpr (HAS_X) x = a.x_ptrs ? a.x_ptrs[ch.tensor] + local : a.x_flat + ch.start;
+    float *__restrict__ w = HAS_DT ? a.w + (uint64_t)k * a.ldw + ch.start : nullptr;
     float *__restrict__ e = a.e + (uint64_t)k * a.ld + ch.start;
     float *__restrict__ m = HAS_MU ? a.m + (uint64_t)k * a.ld + ch.start : nullptr;
     float *__restrict__ msg = a.msg + (uint64_t)k * a.ldmsg;
@@ -246,7 +270,7 @@ __global__ __launch_bounds__(THREADS) void def_stream_elem_kernel(DefStepArgs a,
             gv[u] = load1<NT>(g + o);
             if constexpr (HAS_MU) mv[u] = load1<NT>(m + o);
             ev[u] = load1<NT>(e + o);
-            if constexpr (HAS_WD) xv[u] = x[o];
+            if constexpr (HAS_X) xv[u] = x[o];
         }
     }
 #pragma unroll
@@ -264,6 +288,10 @@ __global__ __launch_bounds__(THREADS) void def_stream_elem_kernel(DefStepArgs a,
         }
         if constexpr (HAS_MU) store1<NT>(m + o, mc);
         store1<NT>(e + o, en);
+        if constexpr (HAS_DT) {
+            const float scaled = a.lam * en;                  // see the vectorised kernel
+            store1<NT>(w + o, xv[u] - scaled);
+        }
     }
 }
 
@@ -315,7 +343,14 @@ __global__ __launch_bounds__(DEF_THREADS) void def_average_update_kernel(DefStep
         uint64_t i = a.s + j;
         if (i >= a.d) i -= a.d;
         float *px = param_addr(a, i);
-        *px = *px - cbar;                                     // x_{t+1} = x_t - C(p_t)
+        const float x_new = *px - cbar;                       // x_{t+1} = x_t - C(p_t)
+        *px = x_new;
+        if (a.w) {
+            // inside the block e_{k,t+1} = +0 for every worker: w_k = x_{t+1} - lambda*0
+            const float scaled = a.lam * 0.0f;
+            const float wv = x_new - scaled;
+            for (uint32_t k = 0; k < a.W; ++k) a.w[(uint64_t)k * a.ldw + i] = wv;
+        }
     }
 }
 
@@ -340,6 +375,37 @@ __global__ __launch_bounds__(DEF_THREADS) void def_output_kernel(DefStepArgs a, 
     }
 }
 
+// ---------------------------------------------------------------------------
+// Detached evaluation points for the current state, w_k = x - lambda*e_k
+// (Algorithm 1, "detach" line).  blockIdx.y is the worker, one thread per 4 columns.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(DEF_THREADS) void def_detach_kernel(DefStepArgs a, int vec_xw)
+{
+    const uint64_t i = ((uint64_t)blockIdx.x * DEF_THREADS + threadIdx.x) * 4;
+    if (i >= a.d) return;
+    for (uint32_t k = blockIdx.y; k < a.W; k += gridDim.y) {
+        const v4f ev = load4<false>(a.e + (uint64_t)k * a.ld + i);   // padded rows: always in bounds
+        float *w = a.w + (uint64_t)k * a.ldw;
+        if (vec_xw && i + 4 <= a.d) {
+            const v4f xv = load4<false>(a.x_flat + i);
+            v4f wv;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const float scaled = a.lam * ev[c];
+                wv[c] = xv[c] - scaled;
+            }
+            store4<false>(w + i, wv);
+        } else {
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+                if (i + c < a.d) {
+                    const float scaled = a.lam * ev[c];
+                    w[i + c] = *param_addr(a, i + c) - scaled;
+                }
+        }
+    }
+}
+
 uint32_t grid_for(uint64_t total)
 {
     return (uint32_t)((total + 7) / 8 * 8);                   // the XCD maps need a multiple of 8
@@ -349,43 +415,58 @@ uint32_t grid_for(uint64_t total)
 
 void def_describe_stream_kernel(const DefStepArgs &a, bool vec, char *out, size_t cap)
 {
-    const int mu = a.mu != 0.0f, wd = a.wd != 0.0f;
+    const int mu = a.mu != 0.0f, wd = a.wd != 0.0f, dt = a.w != nullptr;
+    const bool shares_x = wd || dt;
     if (vec) {
         char order[32];
-        if (wd) std::snprintf(order, sizeof order, "blocked:%u", DEF_SUPER_TILES);
+        if (shares_x) std::snprintf(order, sizeof order, "blocked:%u", DEF_SUPER_TILES);
         else std::snprintf(order, sizeof order, "linear");
-        std::snprintf(out, cap, "def_stream_vec4_kernel<mu=%d,wd=%d,threads=%u,quads=%u,nt=1,order=%s,lds=%u>",
-                      mu, wd, DEF_VEC_THREADS, DEF_VEC_QUADS, order, DEF_VEC_LDS_RESERVE);
+        std::snprintf(out, cap,
+                      "def_stream_vec4_kernel<mu=%d,wd=%d,detach=%d,threads=%u,quads=%u,nt=1,order=%s,lds=%u>",
+                      mu, wd, dt, DEF_VEC_THREADS, DEF_VEC_QUADS, order, DEF_VEC_LDS_RESERVE);
     } else {
-        std::snprintf(out, cap, "def_stream_elem_kernel<mu=%d,wd=%d,threads=%u,chunk=%u,nt=1,order=%s>", mu, wd,
-                      DEF_THREADS, DEF_ELEM_CHUNK, wd ? "blocked" : "linear");
+        std::snprintf(out, cap, "def_stream_elem_kernel<mu=%d,wd=%d,detach=%d,threads=%u,chunk=%u,nt=1,order=%s>",
+                      mu, wd, dt, DEF_THREADS, DEF_ELEM_CHUNK, shares_x ? "blocked" : "linear");
     }
 }
+
+// Picks the instantiation for (momentum, weight decay, detached points).  Whenever x
+// is read by every worker (weight decay, or w = x - lambda*e), the blocked order lets
+// all W workers pass over a piece of x while it sits in L2, so x is fetched from HBM
+// once per step instead of W times; otherwise nothing is shared between workers and
+// the plain row-after-row sweep is fastest.
+#define DEF_DISPATCH(LAUNCH)                                        \
+    do {                                                            \
+        const int sel = (mu ? 4 : 0) | (wd ? 2 : 0) | (dt ? 1 : 0); \
+        switch (sel) {                                              \
+        case 0: LAUNCH(false, false, false, MAP_LINEAR_T, 0u); break;   \
+        case 1: LAUNCH(false, false, true, MAP_BLOCKED, SUPER); break;  \
+        case 2: LAUNCH(false, true, false, MAP_BLOCKED, SUPER); break;  \
+        case 3: LAUNCH(false, true, true, MAP_BLOCKED, SUPER); break;   \
+        case 4: LAUNCH(true, false, false, MAP_LINEAR_T, 0u); break;    \
+        case 5: LAUNCH(true, false, true, MAP_BLOCKED, SUPER); break;   \
+        case 6: LAUNCH(true, true, false, MAP_BLOCKED, SUPER); break;   \
+        default: LAUNCH(true, true, true, MAP_BLOCKED, SUPER); break;   \
+        }                                                           \
+    } while (0)
 
 hipError_t def_launch_stream_vec4(const DefStepArgs &a, hipStream_t st)
 {
     constexpr int U = DEF_VEC_QUADS, T = DEF_VEC_THREADS;
-    // Non-temporal loads and stores for the three streams: they are touched once
-    // per step, and keeping them out of L2 / Infinity Cache is worth +20 % here.
+    constexpr uint32_t SUPER = DEF_SUPER_TILES;
+    // Non-temporal loads and stores for the streams: they are touched once per
+    // step, and keeping them out of L2 / Infinity Cache is worth +20 % here.
     constexpr bool NL = true, NS = true;
     const uint64_t per_tile = (uint64_t)T * U * 4;
     const uint64_t tiles = (a.d + per_tile - 1) / per_tile;
     const uint64_t total = tiles * a.W;
     if (total > 0x7fffffffull - 8) return hipErrorInvalidConfiguration;
     const dim3 grid(grid_for(total)), block(T);
-    const bool mu = a.mu != 0.0f, wd = a.wd != 0.0f;
-    // Without weight decay nothing is shared between workers and the plain
-    // row-after-row sweep is fastest.  With weight decay every worker reads x: the
-    // blocked order lets all W workers pass over a piece of x while it sits in L2,
-    // so x is fetched from HBM once per step instead of W times.
-    if (mu && wd)
-        def_stream_vec4_kernel<true, true, T, U, NL, NS, MAP_BLOCKED><<<grid, block, DEF_VEC_LDS_RESERVE, st>>>(a, tiles, total, DEF_SUPER_TILES);
-    else if (mu)
-        def_stream_vec4_kernel<true, false, T, U, NL, NS, MAP_LINEAR_T><<<grid, block, DEF_VEC_LDS_RESERVE, st>>>(a, tiles, total, 0);
-    else if (wd)
-        def_stream_vec4_kernel<false, true, T, U, NL, NS, MAP_BLOCKED><<<grid, block, DEF_VEC_LDS_RESERVE, st>>>(a, tiles, total, DEF_SUPER_TILES);
-    else
-        def_stream_vec4_kernel<false, false, T, U, NL, NS, MAP_LINEAR_T><<<grid, block, DEF_VEC_LDS_RESERVE, st>>>(a, tiles, total, 0);
+    const bool mu = a.mu != 0.0f, wd = a.wd != 0.0f, dt = a.w != nullptr;
+#define DEF_LAUNCH_VEC(MU, WD, DT, MAP, SUP) \
+    def_stream_vec4_kernel<MU, WD, DT, T, U, NL, NS, MAP><<<grid, block, DEF_VEC_LDS_RESERVE, st>>>(a, tiles, total, SUP)
+    DEF_DISPATCH(DEF_LAUNCH_VEC);
+#undef DEF_LAUNCH_VEC
     return hipGetLastError();
 }
 
@@ -398,11 +479,11 @@ hipError_t def_launch_stream_elem(const DefStepArgs &a, hipStream_t st)
     const uint64_t total = (uint64_t)a.n_chunks * a.W;
     if (total > 0x7fffffffull - 8) return hipErrorInvalidConfiguration;
     const dim3 grid(grid_for(total)), block(T);
-    const bool mu = a.mu != 0.0f, wd = a.wd != 0.0f;
-    if (mu && wd) def_stream_elem_kernel<true, true, T, PER, true, MAP_BLOCKED><<<grid, block, 0, st>>>(a, total, SUPER);
-    else if (mu) def_stream_elem_kernel<true, false, T, PER, true, MAP_LINEAR_T><<<grid, block, 0, st>>>(a, total, 0);
-    else if (wd) def_stream_elem_kernel<false, true, T, PER, true, MAP_BLOCKED><<<grid, block, 0, st>>>(a, total, SUPER);
-    else def_stream_elem_kernel<false, false, T, PER, true, MAP_LINEAR_T><<<grid, block, 0, st>>>(a, total, 0);
+    const bool mu = a.mu != 0.0f, wd = a.wd != 0.0f, dt = a.w != nullptr;
+#define DEF_LAUNCH_ELEM(MU, WD, DT, MAP, SUP) \
+    def_stream_elem_kernel<MU, WD, DT, T, PER, true, MAP><<<grid, block, 0, st>>>(a, total, SUP)
+    DEF_DISPATCH(DEF_LAUNCH_ELEM);
+#undef DEF_LAUNCH_ELEM
     return hipGetLastError();
 }
 
@@ -411,6 +492,17 @@ hipError_t def_launch_average_update(const DefStepArgs &a, hipStream_t st)
     const uint64_t tiles = (a.B + DEF_AVG_TILE - 1) / DEF_AVG_TILE;
     if (tiles > 0x7fffffffull) return hipErrorInvalidConfiguration;
     def_average_update_kernel<<<dim3((uint32_t)tiles), dim3(DEF_THREADS), 0, st>>>(a);
+    return hipGetLastError();
+}
+
+hipError_t def_launch_detach(const DefStepArgs &a, hipStream_t st)
+{
+    const uint64_t quads = (a.d + 3) / 4;
+    const uint64_t blocks = (quads + DEF_THREADS - 1) / DEF_THREADS;
+    if (blocks > 0x7fffffffull) return hipErrorInvalidConfiguration;
+    const int vec_xw = a.x_flat != nullptr && ((uintptr_t)a.x_flat % 16 == 0) &&
+                       ((uintptr_t)a.w % 16 == 0) && a.ldw % 4 == 0;
+    def_detach_kernel<<<dim3((uint32_t)blocks, a.W < 65535u ? a.W : 65535u), dim3(DEF_THREADS), 0, st>>>(a, vec_xw);
     return hipGetLastError();
 }
 

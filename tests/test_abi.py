@@ -113,3 +113,10 @@ def test_null_handles_are_rejected(lib):
 def test_missing_library_fails_loudly(tmp_path):
     with pytest.raises(RuntimeError, match="no CPU fallback"):
         binding.load_library(str(tmp_path / "libdef_hip.so"))
+
+
+def test_init_rejects_problems_whose_grid_would_not_fit(lib):
+    """W * ceil(d/256) must stay below 2^31; refused before anything is allocated."""
+    h = ctypes.c_void_p()
+    assert lib.def_init(ctypes.byref(h), ctypes.byref(_cfg(d=2**39, W=64))) == binding.DEF_EINVAL
+    assert not h.value

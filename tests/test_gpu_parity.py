@@ -42,7 +42,7 @@ def fetch_avg(ctx):
 
 def run_case(dev, w, *, weight_decay=None, momentum=None, T=None, flat_params=True,
              mode="flat", misalign=0, ld=None, oracle="np", check_every_step=True,
-             with_y=True, special=None, variant=None, forced=None):
+             with_y=True, special=None, variant=None, forced=None, detach=None, ldw=None):
     """Run T steps on both sides and compare.  mode: "flat" (one gradient buffer
     [W][ld]) or "tensors" (one allocation per worker and tensor)."""
     binding = _binding()
@@ -87,6 +87,10 @@ def run_case(dev, w, *, weight_decay=None, momentum=None, T=None, flat_params=Tr
                     tensors.append(buf[pad:])
             gdev.append(tensors)
     y_dev = torch.full((d,), float("nan"), dtype=torch.float32, device=dev)
+    w_dev = None
+    if detach is not None:
+        ldw = wl.padded_ld(d) if ldw is None else ldw
+        w_dev = torch.full((W, ldw), float("nan"), dtype=torch.float32, device=dev)
 
     if oracle == "np":
         ora = DefOracle(x0, W, w.R, w.lr, mu, wd, w.seed)
@@ -101,6 +105,8 @@ def run_case(dev, w, *, weight_decay=None, momentum=None, T=None, flat_params=Tr
         e_ptr, m_ptr, a_ptr, ld_state = ctx.state_ptrs()
         assert ld_state >= d and ld_state % 64 == 0
         assert (m_ptr != 0) == (mu != 0)
+        if detach is not None:
+            ctx.set_detach(w_dev, ldw, detach)
         for t in range(T):
             g_host = pool[t % w.pool]
             start = (forced or w.forced_start)(t)
@@ -133,14 +139,21 @@ def run_case(dev, w, *, weight_decay=None, momentum=None, T=None, flat_params=Tr
                 # error-memory zeroing: literal +0 inside the block, for every worker
                 assert (bits(e[:, :d][:, mask]) == 0).all(), f"t={t}: block not zeroed"
                 assert not e[:, d:].any(), "padding columns of e must stay zero"
+                if detach is not None:
+                    wg = w_dev.cpu().numpy()[:, :d]
+                    assert_close(f"detached points t={t}", wg, ora.detached_points(detach))
+                    exact.setdefault("w", True)
+                    exact["w"] &= bit_equal(wg, ora.detached_points(detach))
                 if want_y:
                     assert_close(f"y t={t}", y_dev.cpu().numpy(), ora.y())
                     exact.setdefault("y", True)
                     exact["y"] &= bit_equal(y_dev.cpu().numpy(), ora.y())
         torch.cuda.synchronize()
         if mode == "flat":
+            reads_x = wd != 0 or detach is not None
             assert ctx.last_path_vectorised() == (misalign % 4 == 0 and ld % 4 == 0
-                                                  and (flat_params or wd == 0))
+                                                  and (flat_params or not reads_x)
+                                                  and (detach is None or ldw % 4 == 0))
         else:
             assert not ctx.last_path_vectorised()
         e, m, _ = fetch_state(ctx, W, d)
@@ -160,6 +173,15 @@ def run_case(dev, w, *, weight_decay=None, momentum=None, T=None, flat_params=Tr
             ctx.output(y_dev)
             torch.cuda.synchronize()
             assert_close("y (def_output)", y_dev.cpu().numpy(), ora.y())
+        if detach is not None:
+            # the stand-alone call, with another lambda, on the final state
+            w2 = torch.full((W, d + 3), float("nan"), dtype=torch.float32, device=dev)
+            ctx.detach(w2, d + 3, 0.75)
+            torch.cuda.synchronize()
+            assert_close("def_detach", w2.cpu().numpy()[:, :d], ora.detached_points(0.75))
+            assert torch.isnan(w2[:, d:]).all(), "def_detach wrote past column d"
+            if ldw > d:
+                assert torch.isnan(w_dev[:, d:]).all(), "the step wrote w past column d"
     finally:
         ctx.destroy()
     print(f"[parity] {w.name} mode={mode} misalign={misalign} wd={wd} mu={mu} T={T}: bit-identical {exact}",
@@ -244,6 +266,44 @@ def test_hyperparameter_paths(dev, mu, wd, mode):
     exact = run_case(dev, w, momentum=mu, weight_decay=wd, mode=mode,
                      flat_params=(mode == "flat"))
     assert exact["x"] and exact["e"], exact
+
+
+# --------------------------------------------------------------------------- #
+# Detached evaluation points written in the same pass (Algorithm 1, "detach" line).
+# --------------------------------------------------------------------------- #
+@pytest.mark.parametrize("name,d,L,lam,mode,kw", [
+    ("resnet50_shaped", 45057, 21, 0.3, "flat", {}),
+    ("resnet18_shaped", 40009, 9, 0.3, "flat", {}),
+    ("resnet56_shaped", 20001, 7, 1.0, "flat", dict(momentum=0.0)),
+    ("vgg16_shaped", 30003, 5, 0.0, "flat", {}),
+    ("resnet50_shaped", 30011, 9, 0.3, "flat", dict(misalign=1)),
+    ("resnet50_shaped", 30011, 9, 0.5, "flat", dict(ldw=30011)),
+    ("resnet18_shaped", 25003, 11, 0.3, "tensors", dict(flat_params=False)),
+    ("resnet50_shaped", 25003, 11, 0.3, "tensors", dict(flat_params=False)),
+], ids=["wd", "no-wd", "no-momentum-lam1", "lam0", "misaligned-g", "odd-ldw", "tensors", "tensors-wd"])
+def test_detached_points_in_the_same_pass(dev, name, d, L, lam, mode, kw):
+    base = wl.by_name(name)
+    w = wl.shrunk(base, d=d, n_tensors=L, W=min(base.W, 6), T=8, pool=2)
+    exact = run_case(dev, w, mode=mode, detach=lam, forced=lambda t: {2: d - 5, 5: 0}.get(t), **kw)
+    assert exact["w"] and exact["x"] and exact["e"], exact
+
+
+def test_detach_rejects_bad_arguments(dev):
+    binding = _binding()
+    d, W = 1000, 2
+    x = torch.zeros(d, device=dev)
+    wbuf = torch.zeros(W, 1024, device=dev)
+    ctx = binding.DefContext(d, W, 4, 0.1, 0.9, 0.0, 1, params=x,
+                             stream=torch.cuda.current_stream().cuda_stream)
+    for call in (lambda: ctx.set_detach(wbuf, 999, 0.3), lambda: ctx.set_detach(wbuf, 1024, 1.5),
+                 lambda: ctx.set_detach(wbuf, 1024, -0.1), lambda: ctx.set_detach(wbuf, 1024, float("nan")),
+                 lambda: ctx.detach(None, 1024, 0.3), lambda: ctx.detach(wbuf.data_ptr() + 2, 1024, 0.3)):
+        with pytest.raises(binding.DefError) as ei:
+            call()
+        assert ei.value.status == binding.DEF_EINVAL
+    ctx.set_detach(wbuf, 1024, 0.3)
+    ctx.set_detach(None)
+    ctx.destroy()
 
 
 def test_every_wrap_position_small(dev):
