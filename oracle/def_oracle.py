@@ -167,6 +167,24 @@ class DefOracle:
             out[k] = self.x - lam * self.e[k]
         return out
 
+    def diagnostics(self, lam: float) -> dict:
+        """Error-memory statistics of Sec. 3.2 / Appendix A, in float64 from the
+        stored error memories: with e_t = (1/K) sum_k e_k,
+          bar_sq   = ||e_t||^2                      (EF's distance ||x_t - y_t||^2)
+          mean_sq  = (1/K) sum_k ||e_k||^2
+          lam_star = bar_sq / mean_sq               (lambda*(t), Sec. 3.2 item (2))
+          dist     = (1/K) sum_k ||e_t - lam*e_k||^2   (Eq. "min d"), summed directly."""
+        e = self.e.astype(np.float64)
+        acc = np.zeros(e.shape[1], dtype=np.float64)
+        for k in range(self.W):
+            acc = acc + e[k]
+        e_bar = acc / np.float64(self.W)
+        bar_sq = float(np.sum(e_bar * e_bar))
+        mean_sq = float(sum(np.sum(e[k] * e[k]) for k in range(self.W)) / self.W)
+        dist = float(sum(np.sum((e_bar - np.float64(lam) * e[k]) ** 2) for k in range(self.W)) / self.W)
+        return dict(bar_sq=bar_sq, mean_sq=mean_sq,
+                    lam_star=(bar_sq / mean_sq if mean_sq > 0 else 0.0), dist=dist)
+
     def compact_block(self) -> np.ndarray:
         """The averaged block of the last step as the B-vector that would be
         all-reduced: entry j belongs to global index (s+j) mod d.  Needs the

@@ -38,7 +38,17 @@ def _pin_calls():
         calls.append(lambda k=kind: pins.test_detached_points_special_cases(k))
     calls.append(lambda: pins.test_detached_points_distance_identity())
     calls.append(lambda: pins.test_closed_loop_single_worker_follows_gradient_descent("np64", 1e-12))
+    calls.append(lambda: _diag_pin(np.float64))
     return calls
+
+
+def _diag_pin(dtype):
+    saved = pins.DefOracle
+    pins.DefOracle = pins.NUMPY_ORACLE
+    try:
+        pins.test_diagnostics_against_norms_of_detached_points(dtype)
+    finally:
+        pins.DefOracle = saved
 
 
 def _load(src, philox_src=None):
@@ -64,7 +74,7 @@ def _run_pins(mod, ph):
         for call in _pin_calls():
             try:
                 call()
-            except (AssertionError, IndexError, ValueError):
+            except (AssertionError, IndexError, ValueError, ZeroDivisionError):
                 failed += 1
         try:
             pins.test_block_start_is_library_draw_mod_d()
@@ -99,6 +109,10 @@ MUTANTS = [
     ("detach ignores lambda", "out[k] = self.x - lam * self.e[k]", "out[k] = self.x - self.e[k]"),
     ("detach uses momentum", "out[k] = self.x - lam * self.e[k]", "out[k] = self.x - lam * self.m[k]"),
     ("detach uses worker 0", "out[k] = self.x - lam * self.e[k]", "out[k] = self.x - lam * self.e[0]"),
+    ("diagnostics: mean error not divided", "e_bar = acc / np.float64(self.W)", "e_bar = acc"),
+    ("diagnostics: mean_sq is a sum", "for k in range(self.W)) / self.W)\n        dist", "for k in range(self.W)))\n        dist"),
+    ("diagnostics: lambda* inverted", "lam_star=(bar_sq / mean_sq if", "lam_star=(mean_sq / bar_sq if"),
+    ("diagnostics: distance sign", "(e_bar - np.float64(lam) * e[k]) ** 2", "(e_bar + np.float64(lam) * e[k]) ** 2"),
 ]
 
 PHILOX_MUTANTS = [

@@ -356,6 +356,41 @@ def test_detached_points_distance_identity():
     assert dist(lam_star) == pytest.approx(bar_sq * (mean_sq - bar_sq) / mean_sq, rel=1e-10)
 
 
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+def test_diagnostics_against_norms_of_detached_points(dtype):
+    """The statistics of Sec. 3.2 computed another way: distances between the
+    detached points and y with numpy's norm; lambda*(t) as the vertex of the
+    parabola through three of those distances; W = 1 gives lambda* = 1, dist(1) = 0."""
+    d, W, R, T = 70, 4, 6, 12
+    rng = np.random.default_rng(94)
+    o = DefOracle(rng.standard_normal(d), W, R, 0.1, 0.9, 0.0, 5, dtype=dtype)
+    for t in range(T):
+        o.step(rng.standard_normal((W, d)))
+    e64 = o.e.astype(np.float64)
+    x64 = o.x.astype(np.float64)
+    y64 = x64 - e64.mean(axis=0)
+
+    def dist_by_norm(lam):
+        return float(np.mean([np.linalg.norm((x64 - lam * e64[k]) - y64) ** 2 for k in range(W)]))
+
+    for lam in (0.0, 0.3, 1.0):
+        dg = o.diagnostics(lam)
+        assert dg["dist"] == pytest.approx(dist_by_norm(lam), rel=1e-11)
+        assert dg["bar_sq"] == pytest.approx(np.linalg.norm(x64 - y64) ** 2, rel=1e-11)
+        assert dg["mean_sq"] == pytest.approx(np.mean(np.linalg.norm(e64, axis=1) ** 2), rel=1e-11)
+    d0, d1, d2 = dist_by_norm(0.0), dist_by_norm(1.0), dist_by_norm(2.0)
+    a2 = (d2 - 2 * d1 + d0) / 2.0
+    a1 = d1 - d0 - a2
+    assert o.diagnostics(0.3)["lam_star"] == pytest.approx(-a1 / (2 * a2), rel=1e-9)
+    one = DefOracle(rng.standard_normal(d), 1, R, 0.1, 0.9, 0.0, 5, dtype=dtype)
+    for t in range(5):
+        one.step(rng.standard_normal((1, d)))
+    dg = one.diagnostics(1.0)
+    assert dg["lam_star"] == pytest.approx(1.0, rel=1e-12) and dg["dist"] == 0.0
+    fresh = DefOracle(np.zeros(d), 2, R, 0.1, dtype=dtype).diagnostics(0.3)
+    assert fresh == dict(bar_sq=0.0, mean_sq=0.0, lam_star=0.0, dist=0.0)
+
+
 @pytest.mark.parametrize("kind,tol", [("np64", 1e-12), ("np32", 2e-5), ("c32", 2e-5)])
 def test_closed_loop_single_worker_follows_gradient_descent(kind, tol):
     """K = 1, lambda = 1 on f(theta) = 0.5*||theta - c||^2 with the gradient taken at
