@@ -103,6 +103,9 @@ def main() -> int:
     ap.add_argument("--detach", type=float, default=None, metavar="LAMBDA",
                     help="also write the detached evaluation points w_k = x - LAMBDA*e_k in the "
                          "same pass (24 instead of 20 bytes per worker and index)")
+    ap.add_argument("--aux", action="store_true",
+                    help="also time the occasional kernels (DEF output y, stand-alone detached "
+                         "points, error-memory statistics) and report them under aux_kernels")
     ap.add_argument("--elementwise", action="store_true",
                     help="offset the gradient buffers by one float so that the element-wise "
                          "(any-alignment) kernel runs instead of the vectorised one")
@@ -182,6 +185,30 @@ def main() -> int:
     kernel_ms = ctx.profile_end(args.steps)
     vectorised = ctx.last_path_vectorised()
     kernel_name = ctx.last_kernel()
+    aux = None
+    if args.aux:
+        y = torch.empty(w.d, dtype=torch.float32, device="cuda")
+        wbuf = w_out if w_out is not None else torch.empty((w.W, ld), dtype=torch.float32, device="cuda")
+        stats = torch.zeros(4, dtype=torch.float64, device="cuda")
+        state = 4 * w.W * w.d
+
+        def timed(fn, nbytes, reps=20):
+            fn()
+            torch.cuda.synchronize()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            for _ in range(reps):
+                fn()
+            b.record()
+            torch.cuda.synchronize()
+            ms = a.elapsed_time(b) / reps
+            return {"ms": round(ms, 5), "GB/s": round(nbytes / ms / 1e6, 1), "algorithmic_bytes": nbytes}
+
+        aux = {
+            "def_output": timed(lambda: ctx.output(y), state + 8 * w.d),
+            "def_detach": timed(lambda: ctx.detach(wbuf, ld, 0.3), 2 * state + 4 * w.d),
+            "def_diagnostics": timed(lambda: ctx.diagnostics(0.3, stats), state),
+        }
     ctx.destroy()
 
     ab = algorithmic_bytes(w, detach=args.detach is not None)
@@ -210,6 +237,8 @@ def main() -> int:
                      "algorithmic_bytes_per_launch": ab["stream_kernel"],
                      "traffic": MEASURED_TRAFFIC.get((w.name, kernel_name))},
     }
+    if aux is not None:
+        out["aux_kernels"] = aux
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, ld, args.cpu_budget)
         for k in ("value", "steps_per_s"):

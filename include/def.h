@@ -146,6 +146,19 @@ int def_output(def_ctx *ctx, float *y_out);
 int def_set_detach(def_ctx *ctx, float *w_out, uint64_t ldw, float lambda);
 int def_detach(def_ctx *ctx, float *w_out, uint64_t ldw, float lambda);
 
+/*
+ * Error-memory statistics of the current state (Sec. 3.2, items (1)-(3) and
+ * Eq. "min d"; Appendix A, first display), accumulated in float64.  With
+ * e_t = (1/W) sum_k e_k:
+ *   out[0] = ||e_t||^2                       the distance ||x_t - y_t||^2 of plain EF
+ *   out[1] = (1/W) sum_k ||e_k||^2
+ *   out[2] = lambda*(t) = out[0] / out[1]    (0 if out[1] is 0)
+ *   out[3] = (1/W) sum_k ||e_t - lambda*e_k||^2   DEF's average distance at lambda
+ * out: DEVICE, 4 doubles, 8-byte aligned.  Asynchronous like a step; reproducible
+ * from run to run (no atomics).  DEF_EINVAL for lambda outside [0, 1].
+ */
+int def_diagnostics(def_ctx *ctx, float lambda, double *out);
+
 /* Replace the seed (Sec. 1: the seed all workers share).  t keeps counting. */
 int def_set_seed(def_ctx *ctx, uint64_t seed);
 

@@ -42,6 +42,7 @@ SIGNATURES = {
     "def_output": (ctypes.c_int, [_vp, _vp]),
     "def_set_detach": (ctypes.c_int, [_vp, _vp, _u64, _f32]),
     "def_detach": (ctypes.c_int, [_vp, _vp, _u64, _f32]),
+    "def_diagnostics": (ctypes.c_int, [_vp, _f32, _vp]),
     "def_set_seed": (ctypes.c_int, [_vp, _u64]),
     "def_set_lr": (ctypes.c_int, [_vp, _f32]),
     "def_set_step": (ctypes.c_int, [_vp, _u64]),
@@ -211,6 +212,10 @@ class DefContext:
 
     def detach(self, w_out, ldw: int, lam: float) -> None:
         _check(self._lib.def_detach(self._h, _ptr(w_out), ldw, lam), "def_detach")
+
+    def diagnostics(self, lam: float, out) -> None:
+        """out: float64 device tensor with 4 entries (see def_diagnostics)."""
+        _check(self._lib.def_diagnostics(self._h, lam, _ptr(out)), "def_diagnostics")
 
     # -- knobs ----------------------------------------------------------------
     def set_seed(self, seed: int) -> None:

@@ -71,6 +71,7 @@ struct def_ctx {
     hipStream_t stream = nullptr;
     // device state owned by the library
     float *e = nullptr, *m = nullptr, *msg = nullptr, *avg = nullptr;
+    double *diag = nullptr;   // per-workgroup partial sums of def_diagnostics
     uint64_t ld = 0, ldmsg = 0;
     uint64_t *d_off = nullptr;
     DefChunk *d_chunks = nullptr;
@@ -101,6 +102,7 @@ void free_ctx(def_ctx *c)
     (void)hipFree(c->m);
     (void)hipFree(c->msg);
     (void)hipFree(c->avg);
+    (void)hipFree(c->diag);
     (void)hipFree(c->d_off);
     (void)hipFree(c->d_chunks);
     (void)hipFree(c->d_xptrs);
@@ -231,6 +233,7 @@ int def_init(def_ctx **out, const def_config *cfg)
     if (c->mu != 0.0f) DEF_INIT_HIP(hipMalloc((void **)&c->m, state_bytes));
     DEF_INIT_HIP(hipMalloc((void **)&c->msg, msg_bytes));
     DEF_INIT_HIP(hipMalloc((void **)&c->avg, c->ldmsg * sizeof(float)));
+    DEF_INIT_HIP(hipMalloc((void **)&c->diag, def_diag_blocks(c->d) * 2 * sizeof(double)));
     DEF_INIT_HIP(hipMalloc((void **)&c->d_off, (L + 1) * sizeof(uint64_t)));
     DEF_INIT_HIP(hipMalloc((void **)&c->d_chunks, chunks.size() * sizeof(DefChunk)));
     DEF_INIT_HIP(hipMemsetAsync(c->e, 0, state_bytes, c->stream));           // e_{k,0} = 0
@@ -338,6 +341,14 @@ int def_detach(def_ctx *ctx, float *w_out, uint64_t ldw, float lambda)
     DefStepArgs a = base_args(ctx, 0);
     a.w = w_out; a.ldw = ldw; a.lam = lambda;
     DEF_HIP(def_launch_detach(a, ctx->stream));
+    return DEF_OK;
+}
+
+int def_diagnostics(def_ctx *ctx, float lambda, double *out)
+{
+    if (!ctx || !out || (uintptr_t)out % 8 != 0 || !(lambda >= 0.0f && lambda <= 1.0f)) return DEF_EINVAL;
+    DefStepArgs a = base_args(ctx, 0);
+    DEF_HIP(def_launch_diagnostics(a, lambda, ctx->diag, out, ctx->stream));
     return DEF_OK;
 }
 

@@ -82,5 +82,10 @@ hipError_t def_launch_stream_elem(const DefStepArgs &a, hipStream_t st);
 hipError_t def_launch_average_update(const DefStepArgs &a, hipStream_t st);
 // y = x - mean_k e_k.
 hipError_t def_launch_output(const DefStepArgs &a, float *y, hipStream_t st);
+// Error-memory statistics: ||e_t||^2, (1/W) sum_k ||e_k||^2, lambda*(t) and the distance
+// (1/W) sum_k ||e_t - lambda*e_k||^2, as 4 doubles in out.  partials: def_diag_blocks(d) * 2 doubles.
+uint64_t def_diag_blocks(uint64_t d);
+hipError_t def_launch_diagnostics(const DefStepArgs &a, float lambda, double *partials, double *out,
+                                  hipStream_t st);
 // w_k = x - lambda*e_k for the current state (a.w, a.ldw, a.lam).
 hipError_t def_launch_detach(const DefStepArgs &a, hipStream_t st);

@@ -364,10 +364,10 @@ __global__ __launch_bounds__(DEF_THREADS) void def_output_kernel(DefStepArgs a, 
     if (i >= a.d) return;
     v4f acc = (v4f)(0.0f);
 #pragma unroll 8
-    for (uint32_t k = 0; k < a.W; ++k) acc = acc + load4<false>(a.e + (uint64_t)k * a.ld + i);
+    for (uint32_t k = 0; k < a.W; ++k) acc = acc + load4<true>(a.e + (uint64_t)k * a.ld + i);
     const v4f mean = acc / (float)a.W;
     if (vec_xy && i + 4 <= a.d) {
-        store4<false>(y + i, load4<false>(a.x_flat + i) - mean);
+        store4<true>(y + i, load4<false>(a.x_flat + i) - mean);
     } else {
 #pragma unroll
         for (int c = 0; c < 4; ++c)
@@ -384,7 +384,7 @@ __global__ __launch_bounds__(DEF_THREADS) void def_detach_kernel(DefStepArgs a, 
     const uint64_t i = ((uint64_t)blockIdx.x * DEF_THREADS + threadIdx.x) * 4;
     if (i >= a.d) return;
     for (uint32_t k = blockIdx.y; k < a.W; k += gridDim.y) {
-        const v4f ev = load4<false>(a.e + (uint64_t)k * a.ld + i);   // padded rows: always in bounds
+        const v4f ev = load4<true>(a.e + (uint64_t)k * a.ld + i);    // padded rows: always in bounds
         float *w = a.w + (uint64_t)k * a.ldw;
         if (vec_xw && i + 4 <= a.d) {
             const v4f xv = load4<false>(a.x_flat + i);
@@ -394,7 +394,7 @@ __global__ __launch_bounds__(DEF_THREADS) void def_detach_kernel(DefStepArgs a, 
                 const float scaled = a.lam * ev[c];
                 wv[c] = xv[c] - scaled;
             }
-            store4<false>(w + i, wv);
+            store4<true>(w + i, wv);
         } else {
 #pragma unroll
             for (int c = 0; c < 4; ++c)
@@ -403,6 +403,83 @@ __global__ __launch_bounds__(DEF_THREADS) void def_detach_kernel(DefStepArgs a, 
                     w[i + c] = *param_addr(a, i + c) - scaled;
                 }
         }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Error-memory statistics of Sec. 3.2 (items (1)-(3)) and Appendix A, in float64:
+//   S1 = ||e_t||^2 with e_t = (1/W) sum_k e_k,   S2 = sum_k ||e_k||^2.
+// Stage 1: one thread per 4 columns walks the workers in order (so e_t[i] is the
+// same number whatever the launch shape), then the workgroup adds its threads'
+// sums through wave shuffles and LDS and writes one pair per workgroup.
+// Stage 2: one workgroup adds the pairs in a fixed order and derives
+//   mean_sq = S2/W, lambda*(t) = S1/mean_sq,
+//   (1/W) sum_k ||e_t - lambda e_k||^2 = lambda^2 mean_sq - 2 lambda S1 + S1.
+// No atomics: the result is reproducible from run to run.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ double block_sum(double v, double *lds)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off, 64);
+    const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
+    __syncthreads();                       // lds may still be read from a previous call
+    if (lane == 0) lds[wave] = v;
+    __syncthreads();
+    double total = 0.0;
+    if (threadIdx.x == 0)
+        for (uint32_t q = 0; q < DEF_THREADS / 64; ++q) total += lds[q];
+    return total;                          // valid in thread 0
+}
+
+__global__ __launch_bounds__(DEF_THREADS) void def_diag_partial_kernel(DefStepArgs a, double *partials)
+{
+    __shared__ double lds[DEF_THREADS / 64];
+    const uint64_t i = ((uint64_t)blockIdx.x * DEF_THREADS + threadIdx.x) * 4;
+    double s1 = 0.0, s2 = 0.0;
+    if (i < a.d) {
+        double acc[4] = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll 4
+        for (uint32_t k = 0; k < a.W; ++k) {
+            const v4f ev = load4<true>(a.e + (uint64_t)k * a.ld + i);   // padding columns hold zeros
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const double v = (double)ev[c];
+                acc[c] += v;
+                s2 += v * v;
+            }
+        }
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const double mean = acc[c] / (double)a.W;
+            s1 += mean * mean;
+        }
+    }
+    const double b1 = block_sum(s1, lds);
+    const double b2 = block_sum(s2, lds);
+    if (threadIdx.x == 0) {
+        partials[2 * (uint64_t)blockIdx.x] = b1;
+        partials[2 * (uint64_t)blockIdx.x + 1] = b2;
+    }
+}
+
+__global__ __launch_bounds__(DEF_THREADS) void def_diag_final_kernel(const double *partials, uint64_t n,
+                                                                     uint32_t W, float lambda, double *out)
+{
+    __shared__ double lds[DEF_THREADS / 64];
+    double s1 = 0.0, s2 = 0.0;
+    for (uint64_t b = threadIdx.x; b < n; b += DEF_THREADS) {
+        s1 += partials[2 * b];
+        s2 += partials[2 * b + 1];
+    }
+    const double S1 = block_sum(s1, lds);
+    const double S2 = block_sum(s2, lds);
+    if (threadIdx.x == 0) {
+        const double mean_sq = S2 / (double)W;
+        const double lam = (double)lambda;
+        out[0] = S1;
+        out[1] = mean_sq;
+        out[2] = mean_sq > 0.0 ? S1 / mean_sq : 0.0;
+        out[3] = lam * lam * mean_sq - 2.0 * lam * S1 + S1;
     }
 }
 
@@ -492,6 +569,24 @@ hipError_t def_launch_average_update(const DefStepArgs &a, hipStream_t st)
     const uint64_t tiles = (a.B + DEF_AVG_TILE - 1) / DEF_AVG_TILE;
     if (tiles > 0x7fffffffull) return hipErrorInvalidConfiguration;
     def_average_update_kernel<<<dim3((uint32_t)tiles), dim3(DEF_THREADS), 0, st>>>(a);
+    return hipGetLastError();
+}
+
+uint64_t def_diag_blocks(uint64_t d)
+{
+    const uint64_t quads = (d + 3) / 4;
+    return (quads + DEF_THREADS - 1) / DEF_THREADS;
+}
+
+hipError_t def_launch_diagnostics(const DefStepArgs &a, float lambda, double *partials, double *out,
+                                  hipStream_t st)
+{
+    const uint64_t blocks = def_diag_blocks(a.d);
+    if (blocks > 0x7fffffffull) return hipErrorInvalidConfiguration;
+    def_diag_partial_kernel<<<dim3((uint32_t)blocks), dim3(DEF_THREADS), 0, st>>>(a, partials);
+    hipError_t err = hipGetLastError();
+    if (err != hipSuccess) return err;
+    def_diag_final_kernel<<<dim3(1), dim3(DEF_THREADS), 0, st>>>(partials, blocks, a.W, lambda, out);
     return hipGetLastError();
 }
 

@@ -20,6 +20,9 @@ from paper_2004_05298_amd import workloads as wl
 from tests.parity import assert_close, bit_equal, bits, in_block_mask
 
 pytestmark = pytest.mark.gpu
+
+# the C ABI takes lambda as a float: the oracle is given the same binary32 value
+LAM32 = float(np.float32(0.3))
 torch = pytest.importorskip("torch")
 
 
@@ -88,6 +91,16 @@ def test_whole_buffers_against_c_oracle(dev, name):
             ctx.output(y)
             torch.cuda.synchronize()
             assert_close("y", y.cpu().numpy(), ora.y())
+        from oracle.def_oracle import DefOracle
+        diag = torch.zeros(4, dtype=torch.float64, device=dev)
+        ctx.diagnostics(0.3, diag)
+        torch.cuda.synchronize()
+        got, ref = diag.cpu().numpy(), DefOracle.diagnostics(ora, LAM32)
+        assert abs(got[0] - ref["bar_sq"]) <= 1e-10 * ref["mean_sq"], (got, ref)
+        assert abs(got[1] - ref["mean_sq"]) <= 1e-10 * ref["mean_sq"], (got, ref)
+        assert abs(got[2] - ref["lam_star"]) <= 1e-9 and abs(got[3] - ref["dist"]) <= 1e-9 * ref["mean_sq"]
+        print(f"[fullsize] {name}: lambda*(t)={got[2]:.4f} EF distance/DEF distance at 0.3 = {got[0] / got[3]:.3f}",
+              flush=True)
         print(f"[fullsize] {name}: bit-identical x={bit_equal(xg, ora.x)} e={bit_equal(e[:, :d], ora.e)} "
               f"m={bit_equal(m[:, :d], ora.m)} avg={bit_equal(avg, ora.compact_block())}", flush=True)
         assert bit_equal(e[:, :d], ora.e) and bit_equal(m[:, :d], ora.m)

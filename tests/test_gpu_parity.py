@@ -12,6 +12,9 @@ from tests.parity import assert_close, bit_equal, bits, in_block_mask
 
 pytestmark = pytest.mark.gpu
 
+# the C ABI takes lambda as a float: the oracle is given the same binary32 value
+LAM32 = float(np.float32(0.3))
+
 torch = pytest.importorskip("torch")
 
 
@@ -27,6 +30,14 @@ def _binding():
     from paper_2004_05298_amd import binding
     binding.load_library()          # raises if the HIP library is not built: no fallback
     return binding
+
+
+def ora_diag(ora, lam):
+    """Statistics of the oracle's error memories; the C oracle holds the same arrays,
+    so the numpy oracle's routine is applied to them."""
+    if hasattr(ora, "diagnostics"):
+        return ora.diagnostics(lam)
+    return DefOracle.diagnostics(ora, lam)
 
 
 def fetch_state(ctx, W, d):
@@ -173,6 +184,19 @@ def run_case(dev, w, *, weight_decay=None, momentum=None, T=None, flat_params=Tr
             ctx.output(y_dev)
             torch.cuda.synchronize()
             assert_close("y (def_output)", y_dev.cpu().numpy(), ora.y())
+        # error-memory statistics of the final state (float64 sums; only the order in which
+        # columns are added differs from the oracle, so 1e-10 relative is ample; the
+        # distance is formed from the other two and may lose digits to cancellation)
+        if not (special is not None):
+            diag = torch.full((4,), float("nan"), dtype=torch.float64, device=dev)
+            ctx.diagnostics(0.3, diag)
+            torch.cuda.synchronize()
+            got, ref = diag.cpu().numpy(), ora_diag(ora, LAM32)
+            scale = max(ref["mean_sq"], 1e-300)
+            assert abs(got[0] - ref["bar_sq"]) <= 1e-10 * scale, (got, ref)
+            assert abs(got[1] - ref["mean_sq"]) <= 1e-10 * scale, (got, ref)
+            assert abs(got[2] - ref["lam_star"]) <= 1e-9, (got, ref)
+            assert abs(got[3] - ref["dist"]) <= 1e-9 * scale, (got, ref)
         if detach is not None:
             # the stand-alone call, with another lambda, on the final state
             w2 = torch.full((W, d + 3), float("nan"), dtype=torch.float32, device=dev)
