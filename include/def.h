@@ -162,6 +162,36 @@ int def_diagnostics(def_ctx *ctx, float lambda, double *out);
 /* Replace the seed (Sec. 1: the seed all workers share).  t keeps counting. */
 int def_set_seed(def_ctx *ctx, uint64_t seed);
 
+/*
+ * Block draw on the device, for callers that capture steps into a HIP graph.
+ *
+ * By default the start index of a step is drawn on the host when the step is
+ * enqueued and travels as a kernel argument, so a captured step would replay the
+ * same block for ever.  With the device draw switched on, every step begins with
+ * a one-thread kernel that draws s_t from a device-resident copy of (seed, t) -
+ * the same Philox4x64-10 draw - advances t there and hands s_t to the other
+ * kernels through device memory.  A captured step (or run of steps) can then be
+ * replayed: each replay performs the next iteration(s).  A step enqueues only
+ * kernel launches (no memset, no copy, no allocation, no synchronisation), so it
+ * can be captured with hipStreamBeginCapture on the context's stream; gradients
+ * are read from the addresses given at capture time, and eta, lambda and the
+ * output pointers are captured by value (capture again after def_set_lr).  Do not
+ * profile (def_profile_begin) while capturing.
+ *
+ * def_set_device_draw  on != 0: copy the host's (t, seed, pending forced start)
+ *                      to the device and use the device draw from the next step;
+ *                      on == 0: back to the host draw (call def_sync_step first if
+ *                      graphs were replayed).  def_set_seed, def_set_step and
+ *                      def_force_next_start keep working: in this mode they also
+ *                      enqueue a one-thread kernel that updates the device copy.
+ * def_sync_step        replays advance t on the device only.  This call copies the
+ *                      device's t (and the start of the last step) back so that
+ *                      def_get_step and def_last_block are current again.
+ *                      Synchronises the stream; not allowed during capture.
+ */
+int def_set_device_draw(def_ctx *ctx, int on);
+int def_sync_step(def_ctx *ctx);
+
 /* Learning-rate schedules (eta_t in Theorem 1; step decay in Sec. 5 "Settings"). */
 int def_set_lr(def_ctx *ctx, float lr);
 

@@ -44,6 +44,8 @@ SIGNATURES = {
     "def_detach": (ctypes.c_int, [_vp, _vp, _u64, _f32]),
     "def_diagnostics": (ctypes.c_int, [_vp, _f32, _vp]),
     "def_set_seed": (ctypes.c_int, [_vp, _u64]),
+    "def_set_device_draw": (ctypes.c_int, [_vp, ctypes.c_int]),
+    "def_sync_step": (ctypes.c_int, [_vp]),
     "def_set_lr": (ctypes.c_int, [_vp, _f32]),
     "def_set_step": (ctypes.c_int, [_vp, _u64]),
     "def_get_step": (ctypes.c_int, [_vp, ctypes.POINTER(_u64)]),
@@ -220,6 +222,12 @@ class DefContext:
     # -- knobs ----------------------------------------------------------------
     def set_seed(self, seed: int) -> None:
         _check(self._lib.def_set_seed(self._h, seed), "def_set_seed")
+
+    def set_device_draw(self, on: bool) -> None:
+        _check(self._lib.def_set_device_draw(self._h, 1 if on else 0), "def_set_device_draw")
+
+    def sync_step(self) -> None:
+        _check(self._lib.def_sync_step(self._h), "def_sync_step")
 
     def set_lr(self, lr: float) -> None:
         _check(self._lib.def_set_lr(self._h, lr), "def_set_lr")

@@ -72,6 +72,8 @@ struct def_ctx {
     // device state owned by the library
     float *e = nullptr, *m = nullptr, *msg = nullptr, *avg = nullptr;
     double *diag = nullptr;   // per-workgroup partial sums of def_diagnostics
+    DefCtl *ctl = nullptr;    // device copy of (t, seed, forced, s) for the device draw
+    bool device_draw = false;
     uint64_t ld = 0, ldmsg = 0;
     uint64_t *d_off = nullptr;
     DefChunk *d_chunks = nullptr;
@@ -103,6 +105,7 @@ void free_ctx(def_ctx *c)
     (void)hipFree(c->msg);
     (void)hipFree(c->avg);
     (void)hipFree(c->diag);
+    (void)hipFree(c->ctl);
     (void)hipFree(c->d_off);
     (void)hipFree(c->d_chunks);
     (void)hipFree(c->d_xptrs);
@@ -126,6 +129,13 @@ DefStepArgs base_args(const def_ctx *c, uint64_t s)
 // The sequence of one iteration: streaming pass, average + update, optional y.
 int run_step(def_ctx *c, DefStepArgs &a, bool vec, float *y_out)
 {
+    if (c->device_draw) {
+        // the kernels take the start the draw kernel leaves in device memory; a.s, drawn
+        // on the host from the host's copy of (seed, t), is the same number as long as
+        // the host's step counter is current (see def_sync_step)
+        DEF_HIP(def_launch_draw(c->ctl, c->d, c->stream));
+        a.ctl = c->ctl;
+    }
     const bool prof = c->prof_n < c->prof_cap;
     if (prof) DEF_HIP(hipEventRecord(c->ev[2 * c->prof_n], c->stream));
     DEF_HIP(vec ? def_launch_stream_vec4(a, c->stream) : def_launch_stream_elem(a, c->stream));
@@ -234,6 +244,8 @@ int def_init(def_ctx **out, const def_config *cfg)
     DEF_INIT_HIP(hipMalloc((void **)&c->msg, msg_bytes));
     DEF_INIT_HIP(hipMalloc((void **)&c->avg, c->ldmsg * sizeof(float)));
     DEF_INIT_HIP(hipMalloc((void **)&c->diag, def_diag_blocks(c->d) * 2 * sizeof(double)));
+    DEF_INIT_HIP(hipMalloc((void **)&c->ctl, sizeof(DefCtl)));
+    DEF_INIT_HIP(hipMemsetAsync(c->ctl, 0, sizeof(DefCtl), c->stream));
     DEF_INIT_HIP(hipMalloc((void **)&c->d_off, (L + 1) * sizeof(uint64_t)));
     DEF_INIT_HIP(hipMalloc((void **)&c->d_chunks, chunks.size() * sizeof(DefChunk)));
     DEF_INIT_HIP(hipMemsetAsync(c->e, 0, state_bytes, c->stream));           // e_{k,0} = 0
@@ -355,7 +367,35 @@ int def_diagnostics(def_ctx *ctx, float lambda, double *out)
 int def_set_seed(def_ctx *ctx, uint64_t seed)
 {
     if (!ctx) return DEF_EINVAL;
+    if (ctx->device_draw)
+        DEF_HIP(def_launch_ctl_set(ctx->ctl, DEF_CTL_SEED, 0, seed, -1, ctx->stream));
     ctx->seed = seed;
+    return DEF_OK;
+}
+
+int def_set_device_draw(def_ctx *ctx, int on)
+{
+    if (!ctx) return DEF_EINVAL;
+    if (on && !ctx->device_draw)
+        DEF_HIP(def_launch_ctl_set(ctx->ctl, DEF_CTL_T | DEF_CTL_SEED | DEF_CTL_FORCED, ctx->t, ctx->seed,
+                                   ctx->forced, ctx->stream));
+    ctx->device_draw = on != 0;
+    return DEF_OK;
+}
+
+int def_sync_step(def_ctx *ctx)
+{
+    if (!ctx) return DEF_EINVAL;
+    if (!ctx->device_draw) return DEF_OK;
+    DefCtl host;
+    DEF_HIP(hipMemcpyAsync(&host, ctx->ctl, sizeof host, hipMemcpyDeviceToHost, ctx->stream));
+    DEF_HIP(hipStreamSynchronize(ctx->stream));
+    if (host.t != ctx->t) {          // steps ran that the host did not issue itself (graph replays)
+        ctx->last_start = host.s;
+        ctx->has_last = host.t > 0;
+    }
+    ctx->t = host.t;
+    ctx->forced = host.forced;
     return DEF_OK;
 }
 
@@ -369,6 +409,7 @@ int def_set_lr(def_ctx *ctx, float lr)
 int def_set_step(def_ctx *ctx, uint64_t t)
 {
     if (!ctx) return DEF_EINVAL;
+    if (ctx->device_draw) DEF_HIP(def_launch_ctl_set(ctx->ctl, DEF_CTL_T, t, 0, -1, ctx->stream));
     ctx->t = t;
     return DEF_OK;
 }
@@ -384,6 +425,8 @@ int def_force_next_start(def_ctx *ctx, int64_t s)
 {
     if (!ctx) return DEF_EINVAL;
     if (s >= 0 && (uint64_t)s >= ctx->d) return DEF_EINVAL;
+    if (ctx->device_draw)
+        DEF_HIP(def_launch_ctl_set(ctx->ctl, DEF_CTL_FORCED, 0, 0, s < 0 ? -1 : s, ctx->stream));
     ctx->forced = s < 0 ? -1 : s;
     return DEF_OK;
 }

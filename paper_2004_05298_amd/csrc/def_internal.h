@@ -37,12 +37,22 @@ constexpr uint32_t DEF_SUPER_TILES = 16384;
 // 13 per CU 75 % of the HBM peak (same workload, random data).
 constexpr uint32_t DEF_VEC_LDS_RESERVE = 10240;
 
+// Device-resident copy of the draw state, used when the block start is drawn on the
+// device so that a captured HIP graph of a step can be replayed (each replay advances t).
+struct DefCtl {
+    uint64_t t;       // step counter
+    uint64_t seed;    // shared seed
+    int64_t forced;   // >= 0: start to use for the next step only
+    uint64_t s;       // start drawn for the step in flight
+};
+
 // Everything one step needs on the device.
 struct DefStepArgs {
     // problem (notation of Algorithm 1 / Sec. 3.2 of arXiv 2004.05298)
     uint64_t d;        // parameters
     uint64_t B;        // block length
-    uint64_t s;        // block start s_t
+    uint64_t s;        // block start s_t (host draw)
+    const DefCtl *ctl; // not null: the start is ctl->s, drawn on the device by def_launch_draw
     uint32_t W;        // workers
     float lr, mu, wd;  // eta, mu, weight decay
     // library-owned state
@@ -72,6 +82,12 @@ struct DefStepArgs {
 
 // Text describing the instantiation def_launch_stream_vec4 / _elem picks for these arguments.
 void def_describe_stream_kernel(const DefStepArgs &a, bool vec, char *out, size_t cap);
+// Device draw: ctl->s = forced or Philox4x64-10((t,0,0,0),(seed,0))[0] mod d; ++t; forced = -1.
+hipError_t def_launch_draw(DefCtl *ctl, uint64_t d, hipStream_t st);
+// Overwrite the fields of the device draw state selected by mask.
+enum : uint32_t { DEF_CTL_T = 1, DEF_CTL_SEED = 2, DEF_CTL_FORCED = 4 };
+hipError_t def_launch_ctl_set(DefCtl *ctl, uint32_t mask, uint64_t t, uint64_t seed, int64_t forced,
+                              hipStream_t st);
 // Fused momentum + error feedback + compress + residual pass, dwordx4 accesses.
 // Needs: g_flat 16-byte aligned, ldg % 4 == 0; x_flat 16-byte aligned if x is read (wd != 0 or
 // w requested); w 16-byte aligned with ldw % 4 == 0.

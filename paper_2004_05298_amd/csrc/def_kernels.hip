@@ -81,6 +81,13 @@ __device__ __forceinline__ float compensated(float g, float &m, float e, float x
     return step + e;                     // p_{k,t} = eta*m_{k,t+1} + e_{k,t}
 }
 
+// Block start of the step: a kernel argument when the host drew it, else the value
+// the draw kernel left in device memory (one uniform load per wave).
+__device__ __forceinline__ uint64_t block_start_of(const DefStepArgs &a)
+{
+    return a.ctl ? a.ctl->s : a.s;
+}
+
 // Workgroup ids are dealt round-robin to the 8 XCDs.  Work items (one worker's
 // piece of one column tile) are numbered 0..tiles*W-1; MAP chooses how a
 // workgroup id becomes a work item:
@@ -144,6 +151,7 @@ __global__ __launch_bounds__(THREADS) void def_stream_vec4_kernel(DefStepArgs a,
     float *__restrict__ msg = a.msg + (uint64_t)k * a.ldmsg;
     const float *__restrict__ x = a.x_flat;
     float *__restrict__ w = HAS_DT ? a.w + (uint64_t)k * a.ldw : nullptr;
+    const uint64_t s = block_start_of(a);
 
     constexpr uint64_t STRIDE = THREADS * 4;             // elements between a thread's groups
     const uint64_t i_first = (tile * (uint64_t)(THREADS * U) + threadIdx.x) * 4;
@@ -199,7 +207,7 @@ __global__ __launch_bounds__(THREADS) void def_stream_vec4_kernel(DefStepArgs a,
             if constexpr (HAS_MU) mv[u][c] = mc;
         }
         // position of element i inside the circular block: j = (i - s) mod d
-        uint64_t j0 = i >= a.s ? i - a.s : i + a.d - a.s;
+        uint64_t j0 = i >= s ? i - s : i + a.d - s;
         v4f en = p;                                           // off-block: e <- p
         if (!(j0 >= a.B && j0 + 3 < a.d)) {                   // some element may be kept
 #pragma unroll
@@ -259,6 +267,7 @@ __global__ __launch_bounds__(THREADS) void def_stream_elem_kernel(DefStepArgs a,
     float *__restrict__ e = a.e + (uint64_t)k * a.ld + ch.start;
     float *__restrict__ m = HAS_MU ? a.m + (uint64_t)k * a.ld + ch.start : nullptr;
     float *__restrict__ msg = a.msg + (uint64_t)k * a.ldmsg;
+    const uint64_t s = block_start_of(a);
 
     // the host cuts chunks of at most THREADS*PER indices
     float gv[PER], mv[PER], ev[PER], xv[PER];
@@ -280,7 +289,7 @@ __global__ __launch_bounds__(THREADS) void def_stream_elem_kernel(DefStepArgs a,
         float mc = mv[u];
         const float p = compensated<HAS_MU, HAS_WD>(gv[u], mc, ev[u], xv[u], a.lr, a.mu, a.wd);
         const uint64_t i = ch.start + o;
-        const uint64_t j = i >= a.s ? i - a.s : i + a.d - a.s;
+        const uint64_t j = i >= s ? i - s : i + a.d - s;
         float en = p;
         if (j < a.B) {
             msg[j] = p;
@@ -340,7 +349,7 @@ __global__ __launch_bounds__(DEF_THREADS) void def_average_update_kernel(DefStep
     if (j < a.B) {
         const float cbar = acc / (float)a.W;                  // (1/W) sum_k C(p_k)
         a.avg[j] = cbar;
-        uint64_t i = a.s + j;
+        uint64_t i = block_start_of(a) + j;
         if (i >= a.d) i -= a.d;
         float *px = param_addr(a, i);
         const float x_new = *px - cbar;                       // x_{t+1} = x_t - C(p_t)
@@ -483,6 +492,43 @@ __global__ __launch_bounds__(DEF_THREADS) void def_diag_final_kernel(const doubl
     }
 }
 
+// ---------------------------------------------------------------------------
+// Block draw on the device (Sec. 1: one uniformly sampled start index, same seed
+// for all workers).  Philox4x64-10 (Salmon et al., SC 2011) with counter (t,0,0,0)
+// and key (seed,0); the first output word mod d.
+// ---------------------------------------------------------------------------
+__global__ void def_draw_kernel(DefCtl *ctl, uint64_t d)
+{
+    if (threadIdx.x != 0 || blockIdx.x != 0) return;
+    uint64_t start;
+    if (ctl->forced >= 0) {
+        start = (uint64_t)ctl->forced;
+    } else {
+        const uint64_t mul0 = 0xD2E7470EE14C6C93ull, mul1 = 0xCA5A826395121157ull;
+        uint64_t c0 = ctl->t, c1 = 0, c2 = 0, c3 = 0, k0 = ctl->seed, k1 = 0;
+        for (int round = 0; round < 10; ++round) {
+            const uint64_t hi0 = __umul64hi(mul0, c0), lo0 = mul0 * c0;
+            const uint64_t hi1 = __umul64hi(mul1, c2), lo1 = mul1 * c2;
+            const uint64_t n0 = hi1 ^ c1 ^ k0, n2 = hi0 ^ c3 ^ k1;
+            c0 = n0; c1 = lo1; c2 = n2; c3 = lo0;
+            k0 += 0x9E3779B97F4A7C15ull;
+            k1 += 0xBB67AE8584CAA73Bull;
+        }
+        start = c0 % d;
+    }
+    ctl->s = start;
+    ctl->t = ctl->t + 1;
+    ctl->forced = -1;
+}
+
+__global__ void def_ctl_set_kernel(DefCtl *ctl, uint32_t mask, uint64_t t, uint64_t seed, int64_t forced)
+{
+    if (threadIdx.x != 0 || blockIdx.x != 0) return;
+    if (mask & DEF_CTL_T) ctl->t = t;
+    if (mask & DEF_CTL_SEED) ctl->seed = seed;
+    if (mask & DEF_CTL_FORCED) ctl->forced = forced;
+}
+
 uint32_t grid_for(uint64_t total)
 {
     return (uint32_t)((total + 7) / 8 * 8);                   // the XCD maps need a multiple of 8
@@ -569,6 +615,19 @@ hipError_t def_launch_average_update(const DefStepArgs &a, hipStream_t st)
     const uint64_t tiles = (a.B + DEF_AVG_TILE - 1) / DEF_AVG_TILE;
     if (tiles > 0x7fffffffull) return hipErrorInvalidConfiguration;
     def_average_update_kernel<<<dim3((uint32_t)tiles), dim3(DEF_THREADS), 0, st>>>(a);
+    return hipGetLastError();
+}
+
+hipError_t def_launch_draw(DefCtl *ctl, uint64_t d, hipStream_t st)
+{
+    def_draw_kernel<<<dim3(1), dim3(64), 0, st>>>(ctl, d);
+    return hipGetLastError();
+}
+
+hipError_t def_launch_ctl_set(DefCtl *ctl, uint32_t mask, uint64_t t, uint64_t seed, int64_t forced,
+                              hipStream_t st)
+{
+    def_ctl_set_kernel<<<dim3(1), dim3(64), 0, st>>>(ctl, mask, t, seed, forced);
     return hipGetLastError();
 }
 

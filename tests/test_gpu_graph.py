@@ -1,0 +1,117 @@
+"""Device-side block draw and HIP-graph replay of captured steps, against the CPU
+oracle.  Each replay is followed by a synchronisation and checked on its own, with
+eager work (the copy of the next gradients) between replays."""
+from __future__ import annotations
+
+import numpy as np
+import pytest
+
+from oracle.def_oracle import DefOracle
+from paper_2004_05298_amd import workloads as wl
+from tests.parity import bit_equal
+
+pytestmark = pytest.mark.gpu
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def dev():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    torch.cuda.set_device(0)
+    return torch.device("cuda:0")
+
+
+def _setup(dev, stream, d=30011, W=5, R=9, T=12, wd=1e-4, L=7):
+    from paper_2004_05298_amd import binding
+    binding.load_library()
+    w = wl.shrunk(wl.resnet50_shaped(), d=d, n_tensors=L, W=W, R=R, T=T, pool=4)
+    ld = wl.padded_ld(w.d)
+    x0 = wl.initial_params(w)
+    pool = wl.gradient_pool(w, ld=ld, threads=1)
+    with torch.cuda.stream(stream):
+        x = torch.from_numpy(x0).to(dev)
+        gdev = [torch.from_numpy(g).to(dev) for g in pool]
+    stream.synchronize()
+    ora = DefOracle(x0, w.W, w.R, w.lr, w.momentum, wd, w.seed)
+    ctx = binding.DefContext(w.d, w.W, w.R, w.lr, w.momentum, wd, w.seed, params=x,
+                             tensor_offsets=w.tensor_offsets(), stream=stream.cuda_stream)
+    return w, ld, pool, gdev, x, ora, ctx
+
+
+def _check_state(ctx, x, ora, d, where):
+    e, m, _ = ctx.state_tensors()
+    assert bit_equal(x.cpu().numpy(), ora.x), f"{where}: x"
+    assert bit_equal(e.cpu().numpy()[:, :d], ora.e), f"{where}: e"
+    assert bit_equal(m.cpu().numpy()[:, :d], ora.m), f"{where}: m"
+
+
+def test_device_draw_matches_host_draw_and_oracle(dev):
+    stream = torch.cuda.Stream()
+    w, ld, pool, gdev, x, ora, ctx = _setup(dev, stream)
+    try:
+        ctx.set_device_draw(True)
+        for t in range(w.T):
+            if t == 3:
+                ctx.force_next_start(w.d - 2)
+            if t == 5:
+                ctx.set_seed(4242); ora.set_seed(4242)
+            if t == 8:
+                ctx.set_step(100); ora.set_step(100)
+            if t == 10:
+                ctx.set_device_draw(False)          # host draw again; the host's counter is current
+            ctx.step(gdev[t % w.pool], ld)
+            s = ora.step(pool[t % w.pool][:, :w.d], start=(w.d - 2 if t == 3 else None))
+            ctx.sync_step()
+            assert ctx.last_block() == (s, w.B), t
+            assert ctx.get_step() == ora.t
+        stream.synchronize()
+        _check_state(ctx, x, ora, w.d, "device draw")
+    finally:
+        ctx.destroy()
+
+
+@pytest.mark.parametrize("steps_per_graph", [1, 3])
+def test_graph_replays_follow_the_oracle(dev, steps_per_graph):
+    stream = torch.cuda.Stream()
+    w, ld, pool, gdev, x, ora, ctx = _setup(dev, stream)
+    n = steps_per_graph
+    try:
+        with torch.cuda.stream(stream):
+            static = [torch.zeros_like(gdev[0]) for _ in range(n)]
+            y = torch.zeros(w.d, dtype=torch.float32, device=dev)
+        ctx.set_device_draw(True)
+        # two eager steps first (they also warm the kernels up), then capture
+        for t in range(2):
+            ctx.step(gdev[t % w.pool], ld)
+            ora.step(pool[t % w.pool][:, :w.d])
+        stream.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=stream):
+            for q in range(n):
+                ctx.step(static[q], ld, y if q == n - 1 else None)
+        stream.synchronize()
+        _check_state(ctx, x, ora, w.d, "capture must not execute anything")
+        t = 2
+        for replay in range(5):
+            with torch.cuda.stream(stream):
+                for q in range(n):                   # eager work between replays
+                    static[q].copy_(gdev[(t + q) % w.pool])
+                graph.replay()
+            stream.synchronize()
+            for q in range(n):
+                s = ora.step(pool[(t + q) % w.pool][:, :w.d])
+            t += n
+            _check_state(ctx, x, ora, w.d, f"replay {replay}")
+            assert bit_equal(y.cpu().numpy(), ora.y()), f"replay {replay}: y"
+            ctx.sync_step()
+            assert ctx.get_step() == t and ctx.last_block() == (s, w.B)
+        # eager steps after the replays continue the same sequence
+        for _ in range(2):
+            ctx.step(gdev[t % w.pool], ld)
+            ora.step(pool[t % w.pool][:, :w.d])
+            t += 1
+        stream.synchronize()
+        _check_state(ctx, x, ora, w.d, "eager after replays")
+    finally:
+        ctx.destroy()
