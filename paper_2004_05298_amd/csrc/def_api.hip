@@ -213,6 +213,24 @@ int def_init(def_ctx **out, const def_config *cfg)
     c->ld = round_up(c->d, 64);
     c->ldmsg = round_up(c->B, DEF_AVG_TILE);
 
+#define DEF_INIT_HIP(call)                                                      \
+    do {                                                                        \
+        hipError_t err__ = (call);                                              \
+        if (err__ != hipSuccess) { free_ctx(c); return hip_fail(err__); }       \
+    } while (0)
+
+    const size_t state_bytes = (size_t)c->W * c->ld * sizeof(float);
+    const size_t msg_bytes = (size_t)c->W * c->ldmsg * sizeof(float);
+    DEF_INIT_HIP(hipMalloc((void **)&c->e, state_bytes));
+    if (c->mu != 0.0f) DEF_INIT_HIP(hipMalloc((void **)&c->m, state_bytes));
+    DEF_INIT_HIP(hipMalloc((void **)&c->msg, msg_bytes));
+    DEF_INIT_HIP(hipMalloc((void **)&c->avg, c->ldmsg * sizeof(float)));
+    DEF_INIT_HIP(hipMalloc((void **)&c->diag, def_diag_blocks(c->d) * 2 * sizeof(double)));
+    DEF_INIT_HIP(hipMalloc((void **)&c->ctl, sizeof(DefCtl)));
+    DEF_INIT_HIP(hipMemsetAsync(c->ctl, 0, sizeof(DefCtl), c->stream));
+
+    // (the large device buffers come first so that a problem that does not fit fails
+    // before any host table is built)
     // host tables: offsets and the work list of the element-wise kernel
     std::vector<uint64_t> off(L + 1);
     std::vector<DefChunk> chunks;
@@ -231,21 +249,6 @@ int def_init(def_ctx **out, const def_config *cfg)
     }
     c->n_chunks = (uint32_t)chunks.size();
 
-#define DEF_INIT_HIP(call)                                                      \
-    do {                                                                        \
-        hipError_t err__ = (call);                                              \
-        if (err__ != hipSuccess) { free_ctx(c); return hip_fail(err__); }       \
-    } while (0)
-
-    const size_t state_bytes = (size_t)c->W * c->ld * sizeof(float);
-    const size_t msg_bytes = (size_t)c->W * c->ldmsg * sizeof(float);
-    DEF_INIT_HIP(hipMalloc((void **)&c->e, state_bytes));
-    if (c->mu != 0.0f) DEF_INIT_HIP(hipMalloc((void **)&c->m, state_bytes));
-    DEF_INIT_HIP(hipMalloc((void **)&c->msg, msg_bytes));
-    DEF_INIT_HIP(hipMalloc((void **)&c->avg, c->ldmsg * sizeof(float)));
-    DEF_INIT_HIP(hipMalloc((void **)&c->diag, def_diag_blocks(c->d) * 2 * sizeof(double)));
-    DEF_INIT_HIP(hipMalloc((void **)&c->ctl, sizeof(DefCtl)));
-    DEF_INIT_HIP(hipMemsetAsync(c->ctl, 0, sizeof(DefCtl), c->stream));
     DEF_INIT_HIP(hipMalloc((void **)&c->d_off, (L + 1) * sizeof(uint64_t)));
     DEF_INIT_HIP(hipMalloc((void **)&c->d_chunks, chunks.size() * sizeof(DefChunk)));
     DEF_INIT_HIP(hipMemsetAsync(c->e, 0, state_bytes, c->stream));           // e_{k,0} = 0

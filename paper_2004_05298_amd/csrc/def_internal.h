@@ -36,6 +36,8 @@ constexpr uint32_t DEF_SUPER_TILES = 16384;
 // rewards: uncapped (32 per CU) 78-79 %, 20 per CU 80.4 %, 16 per CU 81 %,
 // 13 per CU 75 % of the HBM peak (same workload, random data).
 constexpr uint32_t DEF_VEC_LDS_RESERVE = 10240;
+// Steps that move more than this many bytes use non-temporal accesses for g, m, e.
+constexpr uint64_t DEF_NT_MIN_BYTES = 1ull << 30;
 
 // Device-resident copy of the draw state, used when the block start is drawn on the
 // device so that a captured HIP graph of a step can be replayed (each replay advances t).

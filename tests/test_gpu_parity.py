@@ -402,6 +402,29 @@ def test_set_seed_lr_step_and_resume(dev):
     assert bit_equal(e2[:, :d], ora.e) and bit_equal(m2[:, :d], ora.m)
 
 
+def test_tensor_mode_with_an_unchanged_pointer_table(dev):
+    """The same gradient tensors every step: the device copy of the pointer table is
+    uploaded once and reused."""
+    base = wl.resnet56_shaped()
+    w = wl.shrunk(base, d=9001, n_tensors=5, W=3, T=5, pool=1)
+    exact = run_case(dev, w, mode="tensors", flat_params=False)
+    assert exact["x"] and exact["e"], exact
+
+
+def test_a_problem_that_does_not_fit_reports_out_of_memory(dev):
+    """hipMalloc failure surfaces as DEF_ENOMEM, leaves no context behind, and the
+    library keeps working afterwards."""
+    binding = _binding()
+    x = torch.zeros(16, device=dev)
+    with pytest.raises(binding.DefError) as ei:
+        binding.DefContext(2**36, 2, 4, 0.1, 0.9, 0.0, 1, params=x,          # 512 GiB per state buffer
+                           stream=torch.cuda.current_stream().cuda_stream)
+    assert ei.value.status == binding.DEF_ENOMEM
+    w = wl.shrunk(wl.tiny(), d=999, n_tensors=2, W=2, T=3, pool=2)
+    exact = run_case(dev, w)
+    assert all(exact.values()), exact
+
+
 def test_invalid_arguments_change_nothing(dev):
     binding = _binding()
     d, W = 1000, 2
