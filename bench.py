@@ -94,8 +94,8 @@ def cpu_baseline(w, ld, budget_s=15.0):
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=500)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="resnet50_shaped")
     ap.add_argument("--variant", default=None, choices=[None, "def", "def_a"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -264,6 +264,8 @@ def main() -> int:
                      "frac": None if achieved is None else round(achieved / HBM_PEAK_GBS, 4),
                      "avg_launch_ms": None if k_avg_ms is None else round(k_avg_ms, 5),
                      "launches": len(kernel_ms) if kernel_ms else 0,
+                     "min_launch_ms": round(min(kernel_ms), 5) if kernel_ms else None,
+                     "median_launch_ms": round(sorted(kernel_ms)[len(kernel_ms) // 2], 5) if kernel_ms else None,
                      "algorithmic_bytes_per_launch": ab["stream_kernel"],
                      "traffic": MEASURED_TRAFFIC.get((w.name, kernel_name))},
     }
