@@ -330,6 +330,36 @@ def test_detach_rejects_bad_arguments(dev):
     ctx.destroy()
 
 
+def _random_cases(n, seed):
+    rng = np.random.default_rng(seed)
+    cases = []
+    for q in range(n):
+        d = int(rng.choice([rng.integers(1, 300), rng.integers(300, 5000), rng.integers(5000, 40000)]))
+        W = int(rng.integers(1, 20))
+        R = int(rng.integers(1, min(d, 300) + 1))
+        mu = float(rng.choice([0.0, 0.5, 0.9]))
+        wd = float(rng.choice([0.0, 1e-3]))
+        mode = str(rng.choice(["flat", "flat", "tensors"]))
+        misalign = int(rng.choice([0, 0, 1, 2, 3])) if mode == "flat" else 0
+        detach = [None, 0.3, 1.0][int(rng.integers(0, 3))]
+        L = int(rng.integers(1, min(d, 9) + 1))
+        cases.append((q, d, W, R, mu, wd, mode, misalign, detach, L))
+    return cases
+
+
+@pytest.mark.parametrize("q,d,W,R,mu,wd,mode,misalign,detach,L", _random_cases(24, 20040529),
+                         ids=lambda v: str(v))
+def test_seeded_random_shapes(dev, q, d, W, R, mu, wd, mode, misalign, detach, L):
+    """A seeded draw of shapes and options: sizes around and below one tile, odd
+    worker counts, every gradient alignment, both modes, with and without the
+    detached points."""
+    w = wl.shrunk(wl.tiny(), d=d, n_tensors=L, W=W, R=R, T=5, pool=3)
+    starts = {1: d - 1, 3: max(0, d - w.B)}               # a wrapped block and one ending at d-1
+    exact = run_case(dev, w, momentum=mu, weight_decay=wd, mode=mode, misalign=misalign,
+                     flat_params=(mode == "flat"), detach=detach, forced=lambda t: starts.get(t))
+    assert exact["x"] and exact["e"], exact
+
+
 def test_every_wrap_position_small(dev):
     """Force each start of a small problem in turn (all wrap positions)."""
     base = wl.tiny()
