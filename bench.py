@@ -110,9 +110,9 @@ def main() -> int:
     ap.add_argument("--aux", action="store_true",
                     help="also time the occasional kernels (DEF output y, stand-alone detached "
                          "points, error-memory statistics) and report them under aux_kernels")
-    ap.add_argument("--elementwise", action="store_true",
-                    help="offset the gradient buffers by one float so that the element-wise "
-                         "(any-alignment) kernel runs instead of the vectorised one")
+    ap.add_argument("--misaligned", action="store_true",
+                    help="offset the gradient buffers by one float (rows 4-byte but not 16-byte "
+                         "aligned)")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="N",
                     help="first run N plain device-to-device copies of a 1 GiB tensor (a kernel of "
                          "known traffic, 2^30 bytes read and 2^30 written per launch, against which "
@@ -148,7 +148,7 @@ def main() -> int:
     ld = wl.padded_ld(w.d)
     x = torch.from_numpy(wl.initial_params(w)).cuda()
     pool = wl.device_gradient_pool(w, ld)
-    if args.elementwise:
+    if args.misaligned:
         shifted = []
         for g in pool:
             buf = torch.empty(g.numel() + 4, dtype=torch.float32, device="cuda")

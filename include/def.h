@@ -89,9 +89,9 @@ int def_destroy(def_ctx *ctx);
  * One DEF iteration (Algorithm 1, inner loop, with the momentum variant).
  *   grads  DEVICE, read-only: worker k's flat gradient g_{k,t} starts at
  *          grads + k*ld; ld >= d elements.  Tensor l sits at +off[l].  Must stay
- *          valid until the stream has executed the step.  If grads is 16-byte
- *          aligned and ld is a multiple of 4 the vectorised path runs; any other
- *          alignment is accepted and takes the element-wise path.
+ *          valid until the stream has executed the step.  Any 4-byte alignment
+ *          and any ld >= d are accepted; 16-byte aligned rows (ld a multiple of 4)
+ *          are fastest.
  *   y_out  DEVICE or NULL.  If not NULL, d floats receive DEF's output
  *          y_{t+1} = x_{t+1} - (1/W) sum_k e_{k,t+1}   (Algorithm 1 "Output";
  *          Sec. 3.2, Eq. "y update").  The paper needs y only when the model is
@@ -135,8 +135,7 @@ int def_output(def_ctx *ctx, float *y_out);
  * def_set_detach  from now on every step also writes, in the same pass,
  *                 w_out[k*ldw + i] = x_{t+1}[i] - lambda * e_{k,t+1}[i]
  *                 for all workers k and indices i.  w_out: DEVICE, [W][ldw] floats,
- *                 ldw >= d, caller-owned, must stay valid while set; 16-byte
- *                 alignment and ldw % 4 == 0 keep the vectorised path.
+ *                 ldw >= d, caller-owned, must stay valid while set.
  *                 w_out == NULL switches it off.  Before the first step the
  *                 points are x_0 itself (e_{k,0} = 0).
  * def_detach      writes the same quantity for the CURRENT state (after a restore,
@@ -229,7 +228,8 @@ int def_block_start(uint64_t seed, uint64_t t, uint64_t d, uint64_t *start);
  */
 int def_state_ptrs(def_ctx *ctx, float **e, float **m, float **avg_block, uint64_t *ld_state);
 
-/* Which path the last step took: 1 = vectorised flat path, 0 = element-wise path. */
+/* Which path the last step took: 1 = vectorised path (flat gradients), 0 = element-wise
+ * path (per-tensor gradients, or per-tensor parameters that the pass has to read). */
 int def_last_path(const def_ctx *ctx, int *vectorised);
 
 /*

@@ -286,11 +286,11 @@ int def_step(def_ctx *ctx, const float *grads, uint64_t ld, float *y_out)
     a.g_flat = grads;
     a.ldg = ld;
     a.g_ptrs = nullptr;
-    // the streaming pass reads x only for weight decay and for the detached points
+    // the streaming pass reads x only for weight decay and for the detached points; the
+    // vectorised kernel needs x as one flat vector then (per-tensor parameters go through
+    // the element-wise kernel)
     const bool reads_x = ctx->wd != 0.0f || ctx->w;
-    const bool x_ok = !reads_x || (ctx->x_flat && (uintptr_t)ctx->x_flat % 16 == 0);
-    const bool w_ok = !ctx->w || ((uintptr_t)ctx->w % 16 == 0 && ctx->ldw % 4 == 0);
-    const bool vec = (uintptr_t)grads % 16 == 0 && ld % 4 == 0 && x_ok && w_ok;
+    const bool vec = !reads_x || ctx->x_flat;
     return run_step(ctx, a, vec, y_out);
 }
 

@@ -91,8 +91,8 @@ enum : uint32_t { DEF_CTL_T = 1, DEF_CTL_SEED = 2, DEF_CTL_FORCED = 4 };
 hipError_t def_launch_ctl_set(DefCtl *ctl, uint32_t mask, uint64_t t, uint64_t seed, int64_t forced,
                               hipStream_t st);
 // Fused momentum + error feedback + compress + residual pass, dwordx4 accesses.
-// Needs: g_flat 16-byte aligned, ldg % 4 == 0; x_flat 16-byte aligned if x is read (wd != 0 or
-// w requested); w 16-byte aligned with ldw % 4 == 0.
+// Needs flat gradients, and flat parameters if x is read (wd != 0 or w requested); any
+// 4-byte alignment of g, x and w.
 hipError_t def_launch_stream_vec4(const DefStepArgs &a, hipStream_t st);
 // Same pass, one dword per access, any alignment, flat or per-tensor pointers.
 hipError_t def_launch_stream_elem(const DefStepArgs &a, hipStream_t st);

@@ -30,8 +30,26 @@
 #pragma clang fp contract(off)
 
 typedef float v4f __attribute__((ext_vector_type(4)));
+// The same four floats at any 4-byte aligned address.  The hardware accepts dwordx4
+// accesses at dword alignment, so caller-owned buffers (gradients, x, w) need not be
+// 16-byte aligned for the vectorised kernel; the library's own rows always are.
+typedef v4f v4f_u __attribute__((aligned(4)));
 
 namespace {
+
+template <bool NT>
+__device__ __forceinline__ v4f load4u(const float *p)
+{
+    if constexpr (NT) return __builtin_nontemporal_load(reinterpret_cast<const v4f_u *>(p));
+    else return *reinterpret_cast<const v4f_u *>(p);
+}
+
+template <bool NT>
+__device__ __forceinline__ void store4u(float *p, v4f v)
+{
+    if constexpr (NT) __builtin_nontemporal_store(v, reinterpret_cast<v4f_u *>(p));
+    else *reinterpret_cast<v4f_u *>(p) = v;
+}
 
 template <bool NT>
 __device__ __forceinline__ v4f load4(const float *p)
@@ -163,10 +181,10 @@ __global__ __launch_bounds__(THREADS) void def_stream_vec4_kernel(DefStepArgs a,
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const uint64_t i = i_first + u * STRIDE;
-            gv[u] = load4<NT_LD>(g + i);
+            gv[u] = load4u<NT_LD>(g + i);
             if constexpr (HAS_MU) mv[u] = load4<NT_LD>(m + i);
             ev[u] = load4<NT_LD>(e + i);
-            if constexpr (HAS_X) xv[u] = load4<false>(x + i);
+            if constexpr (HAS_X) xv[u] = load4u<false>(x + i);
         }
     } else {
         // last tile of the row: a group may be cut by d or lie beyond it.  The
@@ -177,8 +195,8 @@ __global__ __launch_bounds__(THREADS) void def_stream_vec4_kernel(DefStepArgs a,
             const uint64_t i = i_first + u * STRIDE;
             gv[u] = (v4f)(0.0f); mv[u] = (v4f)(0.0f); ev[u] = (v4f)(0.0f); xv[u] = (v4f)(0.0f);
             if (i + 4 <= a.d) {
-                gv[u] = load4<NT_LD>(g + i);
-                if constexpr (HAS_X) xv[u] = load4<false>(x + i);
+                gv[u] = load4u<NT_LD>(g + i);
+                if constexpr (HAS_X) xv[u] = load4u<false>(x + i);
             } else if (i < a.d) {
 #pragma unroll
                 for (int c = 0; c < 4; ++c)
@@ -233,7 +251,7 @@ __global__ __launch_bounds__(THREADS) void def_stream_vec4_kernel(DefStepArgs a,
                 wv[c] = xv[u][c] - scaled;
             }
             if (i + 4 <= a.d) {
-                store4<NT_ST>(w + i, wv);
+                store4u<NT_ST>(w + i, wv);
             } else {
 #pragma unroll
                 for (int c = 0; c < 4; ++c)
