@@ -110,6 +110,10 @@ def main() -> int:
     ap.add_argument("--aux", action="store_true",
                     help="also time the occasional kernels (DEF output y, stand-alone detached "
                          "points, error-memory statistics) and report them under aux_kernels")
+    ap.add_argument("--tensors", action="store_true",
+                    help="give gradients and parameters per tensor (def_step_tensors with a "
+                         "pointer table), each tensor starting on a 256-byte boundary as a "
+                         "framework's allocator would place it")
     ap.add_argument("--misaligned", action="store_true",
                     help="offset the gradient buffers by one float (rows 4-byte but not 16-byte "
                          "aligned)")
@@ -155,12 +159,37 @@ def main() -> int:
             buf[1:1 + g.numel()].copy_(g.view(-1))
             shifted.append(buf[1:1 + g.numel()].view(w.W, ld))
         pool = shifted
+    grad_tables = param_tensors = None
+    if args.tensors:
+        off = [int(v) for v in w.tensor_offsets()]
+        starts, pos = [], 0
+        for l in range(w.n_tensors):
+            starts.append(pos)
+            pos += -(-(off[l + 1] - off[l]) // 64) * 64          # next 256-byte boundary
+        xbuf = torch.zeros(pos, dtype=torch.float32, device="cuda")
+        param_tensors = []
+        for l in range(w.n_tensors):
+            view = xbuf[starts[l]:starts[l] + off[l + 1] - off[l]]
+            view.copy_(x[off[l]:off[l + 1]])
+            param_tensors.append(view)
+        grad_tables = []
+        for g in pool:
+            gbuf = torch.zeros((w.W, pos), dtype=torch.float32, device="cuda")
+            table = []
+            for k in range(w.W):
+                for l in range(w.n_tensors):
+                    view = gbuf[k, starts[l]:starts[l] + off[l + 1] - off[l]]
+                    view.copy_(g[k, off[l]:off[l + 1]])
+                    table.append(view)
+            grad_tables.append(table)
+        pool = None
     side = torch.cuda.Stream() if args.graph else None
     if side is not None:
         side.wait_stream(torch.cuda.current_stream())
         torch.cuda.set_stream(side)
     stream = torch.cuda.current_stream().cuda_stream
-    ctx = binding.DefContext(w.d, w.W, w.R, w.lr, w.momentum, w.weight_decay, w.seed, params=x,
+    ctx = binding.DefContext(w.d, w.W, w.R, w.lr, w.momentum, w.weight_decay, w.seed,
+                             params=None if args.tensors else x, param_tensors=param_tensors,
                              tensor_offsets=w.tensor_offsets(), stream=stream)
 
     w_out = None
@@ -172,7 +201,9 @@ def main() -> int:
         forced = w.forced_start(t)
         if forced is not None:
             ctx.force_next_start(forced)
-        if variant == "def_a":
+        if grad_tables is not None:
+            ctx.step_tensors(grad_tables[t % w.pool], None)
+        elif variant == "def_a":
             ctx.a_step(pool[t % w.pool], ld)
         else:
             ctx.step(pool[t % w.pool], ld, None)
@@ -256,7 +287,7 @@ def main() -> int:
         "config": {"workload": w.name, "d": w.d, "W": w.W, "R": w.R, "B": w.B,
                    "n_tensors": w.n_tensors, "momentum": w.momentum,
                    "weight_decay": w.weight_decay, "lr": w.lr, "variant": variant, "detach_lambda": args.detach,
-                   "gradient_sets": w.pool, "launch": f"hip graph of {args.graph} steps" if args.graph else "eager", "path": "dwordx4" if vectorised else "dword",
+                   "gradient_sets": w.pool, "inputs": "per-tensor pointers" if args.tensors else "flat", "launch": f"hip graph of {args.graph} steps" if args.graph else "eager", "path": "dwordx4" if vectorised else "dword",
                    "algorithmic_bytes_per_step": ab["step"]},
         "roofline": {"bound": "hbm", "kernel": kernel_name,
                      "achieved": None if achieved is None else round(achieved, 2),

@@ -112,9 +112,11 @@ int def_a_step(def_ctx *ctx, const float *grads, uint64_t ld);
  * Tensor mode of the two steps: gradients are given per tensor.
  *   grad_ptrs  HOST array of W*n_tensors DEVICE pointers; entry k*n_tensors + l
  *              is worker k's gradient of tensor l (off[l+1]-off[l] floats, any
- *              4-byte alignment).  The table is copied to the device when it
- *              differs from the one used by the previous call; that copy
- *              synchronises the stream, an unchanged table costs nothing.
+ *              4-byte alignment).  The library keeps the last four distinct tables
+ *              on the device: a table seen before costs nothing, a new one is
+ *              copied to the device with a blocking copy (and, once four are held,
+ *              after a stream synchronisation, since the one it replaces may be
+ *              in use).
  *   y_out      as in def_step (one flat vector of d floats) or NULL.
  * Works with either parameter mode.
  */
@@ -228,8 +230,8 @@ int def_block_start(uint64_t seed, uint64_t t, uint64_t d, uint64_t *start);
  */
 int def_state_ptrs(def_ctx *ctx, float **e, float **m, float **avg_block, uint64_t *ld_state);
 
-/* Which path the last step took: 1 = vectorised path (flat gradients), 0 = element-wise
- * path (per-tensor gradients, or per-tensor parameters that the pass has to read). */
+/* How the last step addressed its inputs: 1 = flat gradient buffer (and flat x if the pass
+ * reads x), 0 = per-tensor pointers resolved through the offset table. */
 int def_last_path(const def_ctx *ctx, int *vectorised);
 
 /*

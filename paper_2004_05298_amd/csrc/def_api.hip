@@ -76,8 +76,7 @@ struct def_ctx {
     bool device_draw = false;
     uint64_t ld = 0, ldmsg = 0;
     uint64_t *d_off = nullptr;
-    DefChunk *d_chunks = nullptr;
-    uint32_t n_chunks = 0;
+    uint32_t *d_tile_tensor = nullptr;   // tensor holding the first index of each tile
     // parameters
     float *x_flat = nullptr;
     float **d_xptrs = nullptr;
@@ -86,8 +85,15 @@ struct def_ctx {
     uint64_t ldw = 0;
     float lam = 0;
     // gradient pointer table (tensor mode)
-    const float **d_gptrs = nullptr;
-    std::vector<const float *> h_gptrs;
+    // a few recently used tables are kept on the device, so that a caller cycling
+    // through a handful of gradient sets pays for each upload once
+    struct GradTable {
+        std::vector<const float *> host;
+        const float **dev = nullptr;
+        uint64_t last_used = 0;
+    };
+    GradTable gtab[DEF_GRAD_TABLES];
+    uint64_t gtab_clock = 0;
     // per-launch timing of the streaming kernel
     std::vector<hipEvent_t> ev;
     uint32_t prof_cap = 0, prof_n = 0;
@@ -107,9 +113,9 @@ void free_ctx(def_ctx *c)
     (void)hipFree(c->diag);
     (void)hipFree(c->ctl);
     (void)hipFree(c->d_off);
-    (void)hipFree(c->d_chunks);
+    (void)hipFree(c->d_tile_tensor);
     (void)hipFree(c->d_xptrs);
-    (void)hipFree(c->d_gptrs);
+    for (auto &tb : c->gtab) (void)hipFree(tb.dev);
     delete c;
 }
 
@@ -121,13 +127,13 @@ DefStepArgs base_args(const def_ctx *c, uint64_t s)
     a.e = c->e; a.m = c->m; a.ld = c->ld;
     a.msg = c->msg; a.ldmsg = c->ldmsg; a.avg = c->avg;
     a.x_flat = c->x_flat; a.x_ptrs = c->d_xptrs; a.off = c->d_off; a.L = c->L;
-    a.chunks = c->d_chunks; a.n_chunks = c->n_chunks;
+    a.tile_tensor = c->d_tile_tensor;
     a.w = c->w; a.ldw = c->ldw; a.lam = c->lam;
     return a;
 }
 
 // The sequence of one iteration: streaming pass, average + update, optional y.
-int run_step(def_ctx *c, DefStepArgs &a, bool vec, float *y_out)
+int run_step(def_ctx *c, DefStepArgs &a, float *y_out)
 {
     if (c->device_draw) {
         // the kernels take the start the draw kernel leaves in device memory; a.s, drawn
@@ -138,7 +144,7 @@ int run_step(def_ctx *c, DefStepArgs &a, bool vec, float *y_out)
     }
     const bool prof = c->prof_n < c->prof_cap;
     if (prof) DEF_HIP(hipEventRecord(c->ev[2 * c->prof_n], c->stream));
-    DEF_HIP(vec ? def_launch_stream_vec4(a, c->stream) : def_launch_stream_elem(a, c->stream));
+    DEF_HIP(def_launch_stream(a, c->stream));
     if (prof) {
         DEF_HIP(hipEventRecord(c->ev[2 * c->prof_n + 1], c->stream));
         ++c->prof_n;
@@ -147,8 +153,9 @@ int run_step(def_ctx *c, DefStepArgs &a, bool vec, float *y_out)
     if (y_out) DEF_HIP(def_launch_output(a, y_out, c->stream));
     c->last_start = a.s;
     c->has_last = true;
-    c->last_vec = vec ? 1 : 0;
-    def_describe_stream_kernel(a, vec, c->kernel_name, sizeof c->kernel_name);
+    // 1: flat addressing; 0: gradients and/or the parameters the pass reads come through tables
+    c->last_vec = (a.g_ptrs || ((a.wd != 0.0f || a.w) && a.x_ptrs)) ? 0 : 1;
+    def_describe_stream_kernel(a, c->kernel_name, sizeof c->kernel_name);
     c->forced = -1;
     ++c->t;
     return DEF_OK;
@@ -194,12 +201,10 @@ int def_init(def_ctx **out, const def_config *cfg)
     }
 
     {
-        // one workgroup per (worker, tile) resp. (worker, chunk): the grid must fit 31 bits
+        // one workgroup per (worker, tile): the grid must fit 31 bits
         const uint64_t grid_limit = 0x7fffffffull - 8;
-        const uint64_t per_tile = DEF_VEC_THREADS * DEF_VEC_QUADS * 4;
-        const uint64_t vec_tiles = (cfg->d + per_tile - 1) / per_tile;
-        const uint64_t max_chunks = cfg->d / DEF_ELEM_CHUNK + L;   // each tensor adds at most one short chunk
-        if (vec_tiles * cfg->W > grid_limit || max_chunks * cfg->W > grid_limit) return DEF_EINVAL;
+        const uint64_t vec_tiles = (cfg->d + DEF_VEC_TILE - 1) / DEF_VEC_TILE;
+        if (vec_tiles * cfg->W > grid_limit) return DEF_EINVAL;
     }
 
     def_ctx *c = new (std::nothrow) def_ctx;
@@ -231,33 +236,32 @@ int def_init(def_ctx **out, const def_config *cfg)
 
     // (the large device buffers come first so that a problem that does not fit fails
     // before any host table is built)
-    // host tables: offsets and the work list of the element-wise kernel
+    // host tables: offsets, and for every tile the tensor that holds its first index
+    const uint64_t n_tiles = (c->d + DEF_VEC_TILE - 1) / DEF_VEC_TILE;
     std::vector<uint64_t> off(L + 1);
-    std::vector<DefChunk> chunks;
+    std::vector<uint32_t> tile_tensor;
     try {
         if (cfg->tensor_offsets) off.assign(cfg->tensor_offsets, cfg->tensor_offsets + L + 1);
         else { off[0] = 0; off[1] = c->d; }
-        for (uint32_t l = 0; l < L; ++l)
-            for (uint64_t a = off[l]; a < off[l + 1]; a += DEF_ELEM_CHUNK) {
-                const uint64_t len = off[l + 1] - a < DEF_ELEM_CHUNK ? off[l + 1] - a : DEF_ELEM_CHUNK;
-                chunks.push_back(DefChunk{a, (uint32_t)len, l});
-            }
-        c->h_gptrs.reserve((size_t)c->W * L);
+        tile_tensor.resize(n_tiles);
+        uint32_t l = 0;
+        for (uint64_t t = 0; t < n_tiles; ++t) {
+            while (t * DEF_VEC_TILE >= off[l + 1]) ++l;
+            tile_tensor[t] = l;
+        }
     } catch (const std::bad_alloc &) {
         free_ctx(c);
         return DEF_ENOMEM;
     }
-    c->n_chunks = (uint32_t)chunks.size();
-
     DEF_INIT_HIP(hipMalloc((void **)&c->d_off, (L + 1) * sizeof(uint64_t)));
-    DEF_INIT_HIP(hipMalloc((void **)&c->d_chunks, chunks.size() * sizeof(DefChunk)));
+    DEF_INIT_HIP(hipMalloc((void **)&c->d_tile_tensor, n_tiles * sizeof(uint32_t)));
     DEF_INIT_HIP(hipMemsetAsync(c->e, 0, state_bytes, c->stream));           // e_{k,0} = 0
     if (c->m) DEF_INIT_HIP(hipMemsetAsync(c->m, 0, state_bytes, c->stream)); // m_{k,0} = 0
     DEF_INIT_HIP(hipMemsetAsync(c->msg, 0, msg_bytes, c->stream));
     DEF_INIT_HIP(hipMemsetAsync(c->avg, 0, c->ldmsg * sizeof(float), c->stream));
     DEF_INIT_HIP(hipMemcpyAsync(c->d_off, off.data(), (L + 1) * sizeof(uint64_t),
                                 hipMemcpyHostToDevice, c->stream));
-    DEF_INIT_HIP(hipMemcpyAsync(c->d_chunks, chunks.data(), chunks.size() * sizeof(DefChunk),
+    DEF_INIT_HIP(hipMemcpyAsync(c->d_tile_tensor, tile_tensor.data(), n_tiles * sizeof(uint32_t),
                                 hipMemcpyHostToDevice, c->stream));
     if (!c->x_flat) {
         DEF_INIT_HIP(hipMalloc((void **)&c->d_xptrs, L * sizeof(float *)));
@@ -286,12 +290,7 @@ int def_step(def_ctx *ctx, const float *grads, uint64_t ld, float *y_out)
     a.g_flat = grads;
     a.ldg = ld;
     a.g_ptrs = nullptr;
-    // the streaming pass reads x only for weight decay and for the detached points; the
-    // vectorised kernel needs x as one flat vector then (per-tensor parameters go through
-    // the element-wise kernel)
-    const bool reads_x = ctx->wd != 0.0f || ctx->w;
-    const bool vec = !reads_x || ctx->x_flat;
-    return run_step(ctx, a, vec, y_out);
+    return run_step(ctx, a, y_out);
 }
 
 int def_a_step(def_ctx *ctx, const float *grads, uint64_t ld)
@@ -306,20 +305,41 @@ int def_step_tensors(def_ctx *ctx, const float *const *grad_ptrs, float *y_out)
     const size_t n = (size_t)ctx->W * ctx->L;
     for (size_t q = 0; q < n; ++q)
         if (!grad_ptrs[q] || (uintptr_t)grad_ptrs[q] % 4 != 0) return DEF_EINVAL;
-    const bool same = ctx->d_gptrs && ctx->h_gptrs.size() == n &&
-                      std::memcmp(ctx->h_gptrs.data(), grad_ptrs, n * sizeof(float *)) == 0;
-    if (!same) {
-        if (!ctx->d_gptrs) DEF_HIP(hipMalloc((void **)&ctx->d_gptrs, n * sizeof(float *)));
-        // the previous table may still be in use by a step in flight
-        DEF_HIP(hipStreamSynchronize(ctx->stream));
-        DEF_HIP(hipMemcpy(ctx->d_gptrs, grad_ptrs, n * sizeof(float *), hipMemcpyHostToDevice));
-        ctx->h_gptrs.assign(grad_ptrs, grad_ptrs + n);
+    def_ctx::GradTable *use = nullptr, *free_slot = nullptr, *oldest = nullptr;
+    for (auto &tb : ctx->gtab) {
+        if (!tb.dev) {
+            if (!free_slot) free_slot = &tb;
+        } else if (tb.host.size() == n &&
+                   std::memcmp(tb.host.data(), grad_ptrs, n * sizeof(float *)) == 0) {
+            use = &tb;
+            break;
+        } else if (!oldest || tb.last_used < oldest->last_used) {
+            oldest = &tb;
+        }
     }
+    if (!use) {
+        def_ctx::GradTable *slot = free_slot ? free_slot : oldest;
+        if (!slot->dev) {
+            DEF_HIP(hipMalloc((void **)&slot->dev, n * sizeof(float *)));
+        } else {
+            // a step in flight may still read the table that is being replaced
+            DEF_HIP(hipStreamSynchronize(ctx->stream));
+        }
+        slot->host.clear();                    // not a valid match until the copy has succeeded
+        DEF_HIP(hipMemcpy(slot->dev, grad_ptrs, n * sizeof(float *), hipMemcpyHostToDevice));
+        try {
+            slot->host.assign(grad_ptrs, grad_ptrs + n);
+        } catch (const std::bad_alloc &) {
+            return DEF_ENOMEM;
+        }
+        use = slot;
+    }
+    use->last_used = ++ctx->gtab_clock;
     DefStepArgs a = base_args(ctx, next_start(ctx));
     a.g_flat = nullptr;
     a.ldg = 0;
-    a.g_ptrs = ctx->d_gptrs;
-    return run_step(ctx, a, false, y_out);
+    a.g_ptrs = use->dev;
+    return run_step(ctx, a, y_out);
 }
 
 int def_a_step_tensors(def_ctx *ctx, const float *const *grad_ptrs)

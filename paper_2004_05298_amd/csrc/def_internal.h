@@ -6,23 +6,16 @@
 #include <stddef.h>
 #include <stdint.h>
 
-// One work item of the element-wise streaming kernel: a run of consecutive flat
-// indices that lies inside one tensor of the model.
-struct DefChunk {
-    uint64_t start;   // first flat index
-    uint32_t len;     // 1..DEF_ELEM_CHUNK
-    uint32_t tensor;  // tensor the run belongs to
-};
-
-constexpr uint32_t DEF_ELEM_CHUNK = 2048;   // elements per chunk of the element-wise kernel
+constexpr uint32_t DEF_GRAD_TABLES = 4;      // gradient pointer tables kept on the device
 constexpr uint32_t DEF_AVG_TILE = 256;      // block columns per workgroup of the averaging kernel
-constexpr uint32_t DEF_THREADS = 256;       // workgroup size of every kernel but the vectorised pass
+constexpr uint32_t DEF_THREADS = 256;       // workgroup size of every kernel but the streaming pass
 // Launch shape of the vectorised streaming kernel.  Measured on MI355X (d = 25.6 M,
 // W = 16): one wave per workgroup with one float4 group per lane beats every larger
 // tile (64x1: 78 % of the 8 TB/s HBM peak, 256x1: 75 %, 256x4: 73 %); stores
 // in particular lose bandwidth when a wave issues several of them back to back.
 constexpr uint32_t DEF_VEC_THREADS = 64;
 constexpr uint32_t DEF_VEC_QUADS = 1;       // float4 groups per thread
+constexpr uint32_t DEF_VEC_TILE = DEF_VEC_THREADS * DEF_VEC_QUADS * 4;   // indices per tile
 // Tiles per super-tile of the blocked work-item order used with weight decay.  One
 // tile is 1 KiB of a row, so a super-tile covers 16 MiB of x; workgroups are dealt
 // round-robin to the 8 XCDs, so each XCD's 4 MiB L2 holds 2 MiB of x while the W
@@ -73,29 +66,26 @@ struct DefStepArgs {
     const float *g_flat;       // flat mode: worker k at g_flat + k*ldg
     uint64_t ldg;
     const float *const *g_ptrs;  // DEVICE table [W][L] (tensor mode), else nullptr
-    // element-wise kernel work list
-    const DefChunk *chunks;
-    uint32_t n_chunks;
+    // tensor that holds the first index of each tile of DEF_VEC_TILE indices (DEVICE)
+    const uint32_t *tile_tensor;
     // detached evaluation points w_k = x - lambda*e_k (nullptr: not requested)
     float *w;                  // [W][ldw]
     uint64_t ldw;
     float lam;
 };
 
-// Text describing the instantiation def_launch_stream_vec4 / _elem picks for these arguments.
-void def_describe_stream_kernel(const DefStepArgs &a, bool vec, char *out, size_t cap);
+// Text describing the instantiation def_launch_stream picks for these arguments.
+void def_describe_stream_kernel(const DefStepArgs &a, char *out, size_t cap);
 // Device draw: ctl->s = forced or Philox4x64-10((t,0,0,0),(seed,0))[0] mod d; ++t; forced = -1.
 hipError_t def_launch_draw(DefCtl *ctl, uint64_t d, hipStream_t st);
 // Overwrite the fields of the device draw state selected by mask.
 enum : uint32_t { DEF_CTL_T = 1, DEF_CTL_SEED = 2, DEF_CTL_FORCED = 4 };
 hipError_t def_launch_ctl_set(DefCtl *ctl, uint32_t mask, uint64_t t, uint64_t seed, int64_t forced,
                               hipStream_t st);
-// Fused momentum + error feedback + compress + residual pass, dwordx4 accesses.
-// Needs flat gradients, and flat parameters if x is read (wd != 0 or w requested); any
-// 4-byte alignment of g, x and w.
-hipError_t def_launch_stream_vec4(const DefStepArgs &a, hipStream_t st);
-// Same pass, one dword per access, any alignment, flat or per-tensor pointers.
-hipError_t def_launch_stream_elem(const DefStepArgs &a, hipStream_t st);
+// Fused momentum + error feedback + compress + residual pass (+ detached points), dwordx4
+// accesses.  Gradients: one buffer (g_flat) or per-tensor pointers (g_ptrs); parameters, if the
+// pass reads them: one vector (x_flat) or per-tensor pointers (x_ptrs).  Any 4-byte alignment.
+hipError_t def_launch_stream(const DefStepArgs &a, hipStream_t st);
 // Cross-worker average of the compact blocks (LDS-staged) and parameter update.
 hipError_t def_launch_average_update(const DefStepArgs &a, hipStream_t st);
 // y = x - mean_k e_k.

@@ -65,20 +65,6 @@ __device__ __forceinline__ void store4(float *p, v4f v)
     else *reinterpret_cast<v4f *>(p) = v;
 }
 
-template <bool NT>
-__device__ __forceinline__ float load1(const float *p)
-{
-    if constexpr (NT) return __builtin_nontemporal_load(p);
-    else return *p;
-}
-
-template <bool NT>
-__device__ __forceinline__ void store1(float *p, float v)
-{
-    if constexpr (NT) __builtin_nontemporal_store(v, p);
-    else *p = v;
-}
-
 // The compensated value p_{k,t}[i]; updates m in place when momentum is on.
 template <bool HAS_MU, bool HAS_WD>
 __device__ __forceinline__ float compensated(float g, float &m, float e, float x,
@@ -150,11 +136,20 @@ __device__ __forceinline__ bool decode_item(uint64_t total, uint64_t tiles, uint
 }
 
 // ---------------------------------------------------------------------------
-// Streaming pass, vectorised.  One workgroup = one worker's tile of
-// THREADS*U float4 groups; thread t owns groups t, t+THREADS, ... so that each wave
-// instruction touches 1 KiB of consecutive memory.
+// Streaming pass.  One workgroup = one worker's tile of THREADS*U float4 groups;
+// thread t owns groups t, t+THREADS, ... so that each wave instruction touches
+// 1 KiB of consecutive memory.
+//
+// TABLES = false: gradients are one buffer [W][ldg] and, if x is read, it is one
+// flat vector.  TABLES = true: gradients and/or parameters are given per tensor.
+// The host supplies, for every tile, the tensor that holds the tile's first index;
+// a tile that lies inside one tensor (nearly all do) only rebases its g and x
+// pointers and then runs the same code as the flat case, with dword-aligned
+// dwordx4 accesses; a tile that crosses a tensor boundary resolves g and x element
+// by element through the offset table.
 // ---------------------------------------------------------------------------
-template <bool HAS_MU, bool HAS_WD, bool HAS_DT, int THREADS, int U, bool NT_LD, bool NT_ST, int MAP>
+template <bool HAS_MU, bool HAS_WD, bool HAS_DT, bool TABLES, int THREADS, int U, bool NT_LD, bool NT_ST,
+          int MAP>
 __global__ __launch_bounds__(THREADS) void def_stream_vec4_kernel(DefStepArgs a, uint64_t tiles,
                                                                   uint64_t total, uint32_t super)
 {
@@ -163,46 +158,87 @@ __global__ __launch_bounds__(THREADS) void def_stream_vec4_kernel(DefStepArgs a,
     uint64_t tile;
     if (!decode_item<MAP>(total, tiles, a.W, super, k, tile)) return;
 
-    const float *__restrict__ g = a.g_flat + (uint64_t)k * a.ldg;
     float *__restrict__ e = a.e + (uint64_t)k * a.ld;
     float *__restrict__ m = HAS_MU ? a.m + (uint64_t)k * a.ld : nullptr;
     float *__restrict__ msg = a.msg + (uint64_t)k * a.ldmsg;
-    const float *__restrict__ x = a.x_flat;
     float *__restrict__ w = HAS_DT ? a.w + (uint64_t)k * a.ldw : nullptr;
     const uint64_t s = block_start_of(a);
 
     constexpr uint64_t STRIDE = THREADS * 4;             // elements between a thread's groups
-    const uint64_t i_first = (tile * (uint64_t)(THREADS * U) + threadIdx.x) * 4;
-    const uint64_t tile_end = (tile + 1) * (uint64_t)(THREADS * U) * 4;
+    constexpr uint64_t TILE = (uint64_t)THREADS * U * 4; // elements per tile
+    const uint64_t i_first = tile * TILE + threadIdx.x * 4;
+    const uint64_t tile_end = (tile + 1) * TILE;
     const bool interior = tile_end <= a.d;
 
+    // g[i - g_sub] and x[i - x_sub] address flat index i on the fast path
+    const float *__restrict__ g = a.g_flat + (uint64_t)k * a.ldg;
+    const float *__restrict__ x = a.x_flat;
+    uint64_t g_sub = 0, x_sub = 0;
+    uint32_t l0 = 0;                                     // tensor of the tile's first index
+    bool one_tensor = true;                              // the tile lies inside one tensor
+    if constexpr (TABLES) {
+        l0 = a.tile_tensor[tile];
+        const uint64_t lo = a.off[l0], hi = a.off[l0 + 1];
+        one_tensor = (interior ? tile_end : a.d) <= hi;
+        if (a.g_ptrs) {
+            g = a.g_ptrs[(uint64_t)k * a.L + l0];
+            g_sub = lo;
+        }
+        if (HAS_X && a.x_ptrs) {
+            x = a.x_ptrs[l0];
+            x_sub = lo;
+        }
+    }
+    // element access for the rare tile that crosses a tensor boundary
+    auto g_at = [&](uint64_t idx) -> float {
+        if constexpr (TABLES) {
+            if (a.g_ptrs) {
+                uint32_t l = l0;
+                while (idx >= a.off[l + 1]) ++l;
+                return a.g_ptrs[(uint64_t)k * a.L + l][idx - a.off[l]];
+            }
+        }
+        return g[idx - g_sub];
+    };
+    auto x_at = [&](uint64_t idx) -> float {
+        if constexpr (TABLES) {
+            if (a.x_ptrs) {
+                uint32_t l = l0;
+                while (idx >= a.off[l + 1]) ++l;
+                return a.x_ptrs[l][idx - a.off[l]];
+            }
+        }
+        return x[idx - x_sub];
+    };
+
     v4f gv[U], mv[U], ev[U], xv[U];
-    if (interior) {
+    if (interior && one_tensor) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const uint64_t i = i_first + u * STRIDE;
-            gv[u] = load4u<NT_LD>(g + i);
+            gv[u] = load4u<NT_LD>(g + (i - g_sub));
             if constexpr (HAS_MU) mv[u] = load4<NT_LD>(m + i);
             ev[u] = load4<NT_LD>(e + i);
-            if constexpr (HAS_X) xv[u] = load4u<false>(x + i);
+            if constexpr (HAS_X) xv[u] = load4u<false>(x + (i - x_sub));
         }
     } else {
-        // last tile of the row: a group may be cut by d or lie beyond it.  The
-        // state rows are padded to a multiple of 64, so e and m can always be
-        // read as whole groups; g and x are read element by element at the cut.
+        // last tile of the row (a group may be cut by d or lie beyond it) or a tile
+        // that crosses a tensor boundary.  The state rows are padded to a multiple of
+        // 64, so e and m can always be read as whole groups; g and x are read
+        // element by element where a group is cut.
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const uint64_t i = i_first + u * STRIDE;
             gv[u] = (v4f)(0.0f); mv[u] = (v4f)(0.0f); ev[u] = (v4f)(0.0f); xv[u] = (v4f)(0.0f);
-            if (i + 4 <= a.d) {
-                gv[u] = load4u<NT_LD>(g + i);
-                if constexpr (HAS_X) xv[u] = load4u<false>(x + i);
+            if (i + 4 <= a.d && one_tensor) {
+                gv[u] = load4u<NT_LD>(g + (i - g_sub));
+                if constexpr (HAS_X) xv[u] = load4u<false>(x + (i - x_sub));
             } else if (i < a.d) {
 #pragma unroll
                 for (int c = 0; c < 4; ++c)
                     if (i + c < a.d) {
-                        gv[u][c] = g[i + c];
-                        if constexpr (HAS_X) xv[u][c] = x[i + c];
+                        gv[u][c] = g_at(i + c);
+                        if constexpr (HAS_X) xv[u][c] = x_at(i + c);
                     }
             }
             if (i < a.d) {
@@ -257,67 +293,6 @@ __global__ __launch_bounds__(THREADS) void def_stream_vec4_kernel(DefStepArgs a,
                 for (int c = 0; c < 4; ++c)
                     if (i + c < a.d) w[i + c] = wv[c];
             }
-        }
-    }
-}
-
-// ---------------------------------------------------------------------------
-// Streaming pass, one dword per access.  Accepts any alignment and per-tensor
-// gradient / parameter pointers; the host cuts the flat index range into chunks
-// that never cross a tensor boundary.
-// ---------------------------------------------------------------------------
-template <bool HAS_MU, bool HAS_WD, bool HAS_DT, int THREADS, int PER, bool NT, int MAP>
-__global__ __launch_bounds__(THREADS) void def_stream_elem_kernel(DefStepArgs a, uint64_t total,
-                                                                  uint32_t super)
-{
-    constexpr bool HAS_X = HAS_WD || HAS_DT;
-    uint32_t k;
-    uint64_t chunk;
-    if (!decode_item<MAP>(total, a.n_chunks, a.W, super, k, chunk)) return;
-    const DefChunk ch = a.chunks[chunk];
-    const uint64_t local = ch.start - a.off[ch.tensor];       // offset inside the tensor
-
-    const float *__restrict__ g = a.g_ptrs ? a.g_ptrs[(uint64_t)k * a.L + ch.tensor] + local
-                                           : a.g_flat + (uint64_t)k * a.ldg + ch.start;
-    const float *__restrict__ x = nullptr;
-    if constexpr (HAS_X) x = a.x_ptrs ? a.x_ptrs[ch.tensor] + local : a.x_flat + ch.start;
-    float *__restrict__ w = HAS_DT ? a.w + (uint64_t)k * a.ldw + ch.start : nullptr;
-    float *__restrict__ e = a.e + (uint64_t)k * a.ld + ch.start;
-    float *__restrict__ m = HAS_MU ? a.m + (uint64_t)k * a.ld + ch.start : nullptr;
-    float *__restrict__ msg = a.msg + (uint64_t)k * a.ldmsg;
-    const uint64_t s = block_start_of(a);
-
-    // the host cuts chunks of at most THREADS*PER indices
-    float gv[PER], mv[PER], ev[PER], xv[PER];
-#pragma unroll
-    for (int u = 0; u < PER; ++u) {
-        const uint32_t o = threadIdx.x + u * THREADS;
-        gv[u] = 0.0f; mv[u] = 0.0f; ev[u] = 0.0f; xv[u] = 0.0f;
-        if (o < ch.len) {
-            gv[u] = load1<NT>(g + o);
-            if constexpr (HAS_MU) mv[u] = load1<NT>(m + o);
-            ev[u] = load1<NT>(e + o);
-            if constexpr (HAS_X) xv[u] = x[o];
-        }
-    }
-#pragma unroll
-    for (int u = 0; u < PER; ++u) {
-        const uint32_t o = threadIdx.x + u * THREADS;
-        if (o >= ch.len) continue;
-        float mc = mv[u];
-        const float p = compensated<HAS_MU, HAS_WD>(gv[u], mc, ev[u], xv[u], a.lr, a.mu, a.wd);
-        const uint64_t i = ch.start + o;
-        const uint64_t j = i >= s ? i - s : i + a.d - s;
-        float en = p;
-        if (j < a.B) {
-            msg[j] = p;
-            en = 0.0f;
-        }
-        if constexpr (HAS_MU) store1<NT>(m + o, mc);
-        store1<NT>(e + o, en);
-        if constexpr (HAS_DT) {
-            const float scaled = a.lam * en;                  // see the vectorised kernel
-            store1<NT>(w + o, xv[u] - scaled);
         }
     }
 }
@@ -564,23 +539,18 @@ static bool streams_non_temporal(const DefStepArgs &a)
     return (uint64_t)a.W * a.d * 20ull > DEF_NT_MIN_BYTES;
 }
 
-void def_describe_stream_kernel(const DefStepArgs &a, bool vec, char *out, size_t cap)
+void def_describe_stream_kernel(const DefStepArgs &a, char *out, size_t cap)
 {
     const int mu = a.mu != 0.0f, wd = a.wd != 0.0f, dt = a.w != nullptr;
-    const bool shares_x = wd || dt;
-    if (vec) {
-        char order[32];
-        if (shares_x) std::snprintf(order, sizeof order, "blocked:%u", DEF_SUPER_TILES);
-        else std::snprintf(order, sizeof order, "linear");
-        std::snprintf(out, cap,
-                      "def_stream_vec4_kernel<mu=%d,wd=%d,detach=%d,threads=%u,quads=%u,nt=%d,order=%s,lds=%u>",
-                      mu, wd, dt, DEF_VEC_THREADS, DEF_VEC_QUADS, (int)streams_non_temporal(a), order,
-                      DEF_VEC_LDS_RESERVE);
-    } else {
-        std::snprintf(out, cap, "def_stream_elem_kernel<mu=%d,wd=%d,detach=%d,threads=%u,chunk=%u,nt=%d,order=%s>",
-                      mu, wd, dt, DEF_THREADS, DEF_ELEM_CHUNK, (int)streams_non_temporal(a),
-                      shares_x ? "blocked" : "linear");
-    }
+    const bool reads_x = wd || dt;
+    const int tables = a.g_ptrs != nullptr || (reads_x && a.x_ptrs != nullptr);
+    char order[32];
+    if (reads_x) std::snprintf(order, sizeof order, "blocked:%u", DEF_SUPER_TILES);
+    else std::snprintf(order, sizeof order, "linear");
+    std::snprintf(out, cap,
+                  "def_stream_vec4_kernel<mu=%d,wd=%d,detach=%d,tables=%d,threads=%u,quads=%u,nt=%d,order=%s,lds=%u>",
+                  mu, wd, dt, tables, DEF_VEC_THREADS, DEF_VEC_QUADS, (int)streams_non_temporal(a), order,
+                  DEF_VEC_LDS_RESERVE);
 }
 
 // Picks the instantiation for (momentum, weight decay, detached points).  Whenever x
@@ -603,7 +573,7 @@ void def_describe_stream_kernel(const DefStepArgs &a, bool vec, char *out, size_
         }                                                           \
     } while (0)
 
-template <bool NT>
+template <bool NT, bool TABLES>
 static void launch_vec4(const DefStepArgs &a, uint64_t tiles, uint64_t total, dim3 grid, dim3 block,
                         hipStream_t st)
 {
@@ -611,44 +581,32 @@ static void launch_vec4(const DefStepArgs &a, uint64_t tiles, uint64_t total, di
     constexpr uint32_t SUPER = DEF_SUPER_TILES;
     const bool mu = a.mu != 0.0f, wd = a.wd != 0.0f, dt = a.w != nullptr;
 #define DEF_LAUNCH_VEC(MU, WD, DT, MAP, SUP) \
-    def_stream_vec4_kernel<MU, WD, DT, T, U, NT, NT, MAP><<<grid, block, DEF_VEC_LDS_RESERVE, st>>>(a, tiles, total, SUP)
+    def_stream_vec4_kernel<MU, WD, DT, TABLES, T, U, NT, NT, MAP><<<grid, block, DEF_VEC_LDS_RESERVE, st>>>(a, tiles, total, SUP)
     DEF_DISPATCH(DEF_LAUNCH_VEC);
 #undef DEF_LAUNCH_VEC
 }
 
-hipError_t def_launch_stream_vec4(const DefStepArgs &a, hipStream_t st)
+static bool uses_tables(const DefStepArgs &a)
 {
-    const uint64_t per_tile = (uint64_t)DEF_VEC_THREADS * DEF_VEC_QUADS * 4;
+    const bool reads_x = a.wd != 0.0f || a.w != nullptr;
+    return a.g_ptrs != nullptr || (reads_x && a.x_ptrs != nullptr);
+}
+
+hipError_t def_launch_stream(const DefStepArgs &a, hipStream_t st)
+{
+    const uint64_t per_tile = DEF_VEC_TILE;
     const uint64_t tiles = (a.d + per_tile - 1) / per_tile;
     const uint64_t total = tiles * a.W;
     if (total > 0x7fffffffull - 8) return hipErrorInvalidConfiguration;
     const dim3 grid(grid_for(total)), block(DEF_VEC_THREADS);
-    if (streams_non_temporal(a)) launch_vec4<true>(a, tiles, total, grid, block, st);
-    else launch_vec4<false>(a, tiles, total, grid, block, st);
-    return hipGetLastError();
-}
-
-template <bool NT>
-static void launch_elem(const DefStepArgs &a, uint64_t total, dim3 grid, dim3 block, hipStream_t st)
-{
-    constexpr int T = DEF_THREADS, PER = DEF_ELEM_CHUNK / DEF_THREADS;
-    static_assert(T * PER >= (int)DEF_ELEM_CHUNK, "a workgroup must cover a whole chunk");
-    // super-tile of the blocked order, in chunks: the same 16 MiB of x as the vectorised kernel
-    constexpr uint32_t SUPER = DEF_SUPER_TILES * DEF_VEC_THREADS * DEF_VEC_QUADS * 4 / DEF_ELEM_CHUNK;
-    const bool mu = a.mu != 0.0f, wd = a.wd != 0.0f, dt = a.w != nullptr;
-#define DEF_LAUNCH_ELEM(MU, WD, DT, MAP, SUP) \
-    def_stream_elem_kernel<MU, WD, DT, T, PER, NT, MAP><<<grid, block, 0, st>>>(a, total, SUP)
-    DEF_DISPATCH(DEF_LAUNCH_ELEM);
-#undef DEF_LAUNCH_ELEM
-}
-
-hipError_t def_launch_stream_elem(const DefStepArgs &a, hipStream_t st)
-{
-    const uint64_t total = (uint64_t)a.n_chunks * a.W;
-    if (total > 0x7fffffffull - 8) return hipErrorInvalidConfiguration;
-    const dim3 grid(grid_for(total)), block(DEF_THREADS);
-    if (streams_non_temporal(a)) launch_elem<true>(a, total, grid, block, st);
-    else launch_elem<false>(a, total, grid, block, st);
+    const bool nt = streams_non_temporal(a);
+    if (uses_tables(a)) {
+        if (nt) launch_vec4<true, true>(a, tiles, total, grid, block, st);
+        else launch_vec4<false, true>(a, tiles, total, grid, block, st);
+    } else {
+        if (nt) launch_vec4<true, false>(a, tiles, total, grid, block, st);
+        else launch_vec4<false, false>(a, tiles, total, grid, block, st);
+    }
     return hipGetLastError();
 }
 

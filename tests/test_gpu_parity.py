@@ -439,6 +439,15 @@ def test_tensor_mode_with_an_unchanged_pointer_table(dev):
     assert exact["x"] and exact["e"], exact
 
 
+def test_tensor_mode_cycling_through_more_tables_than_are_cached(dev):
+    """Six distinct gradient sets with four device slots: tables are evicted and
+    uploaded again while steps are in flight."""
+    base = wl.resnet56_shaped()
+    w = wl.shrunk(base, d=7001, n_tensors=6, W=3, T=14, pool=6)
+    exact = run_case(dev, w, mode="tensors", flat_params=False, check_every_step=False)
+    assert exact["x"] and exact["e"], exact
+
+
 def test_a_problem_that_does_not_fit_reports_out_of_memory(dev):
     """hipMalloc failure surfaces as DEF_ENOMEM, leaves no context behind, and the
     library keeps working afterwards."""
