@@ -356,11 +356,41 @@ __global__ __launch_bounds__(DEF_THREADS) void def_average_update_kernel(DefStep
     }
 }
 
+// x[i..i+3] for a group that may be cut by d (missing entries are 0): flat vector, or
+// per-tensor pointers found through the tile table; dword-aligned dwordx4 when the
+// group lies inside one tensor.
+__device__ __forceinline__ v4f load_x_group(const DefStepArgs &a, uint64_t i)
+{
+    if (i + 4 <= a.d) {
+        if (a.x_flat) return load4u<false>(a.x_flat + i);
+        uint32_t l = a.tile_tensor[i / DEF_VEC_TILE];         // tensor of the tile's first index
+        while (i >= a.off[l + 1]) ++l;
+        if (i + 4 <= a.off[l + 1]) return load4u<false>(a.x_ptrs[l] + (i - a.off[l]));
+    }
+    v4f v = (v4f)(0.0f);
+#pragma unroll
+    for (int c = 0; c < 4; ++c)
+        if (i + c < a.d) v[c] = *param_addr(a, i + c);
+    return v;
+}
+
+// Store a group that may be cut by d to a caller-owned flat vector (any 4-byte alignment).
+__device__ __forceinline__ void store_group(float *dst, uint64_t i, uint64_t d, v4f v)
+{
+    if (i + 4 <= d) {
+        store4u<true>(dst + i, v);
+    } else {
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+            if (i + c < d) dst[i + c] = v[c];
+    }
+}
+
 // ---------------------------------------------------------------------------
 // DEF output y = x - (1/W) sum_k e_k (Algorithm 1 "Output").  One thread owns
 // four consecutive columns and walks the workers in order.
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(DEF_THREADS) void def_output_kernel(DefStepArgs a, float *y, int vec_xy)
+__global__ __launch_bounds__(DEF_THREADS) void def_output_kernel(DefStepArgs a, float *y)
 {
     const uint64_t i = ((uint64_t)blockIdx.x * DEF_THREADS + threadIdx.x) * 4;
     if (i >= a.d) return;
@@ -368,43 +398,27 @@ __global__ __launch_bounds__(DEF_THREADS) void def_output_kernel(DefStepArgs a, 
 #pragma unroll 8
     for (uint32_t k = 0; k < a.W; ++k) acc = acc + load4<true>(a.e + (uint64_t)k * a.ld + i);
     const v4f mean = acc / (float)a.W;
-    if (vec_xy && i + 4 <= a.d) {
-        store4<true>(y + i, load4<false>(a.x_flat + i) - mean);
-    } else {
-#pragma unroll
-        for (int c = 0; c < 4; ++c)
-            if (i + c < a.d) y[i + c] = *param_addr(a, i + c) - mean[c];
-    }
+    store_group(y, i, a.d, load_x_group(a, i) - mean);
 }
 
 // ---------------------------------------------------------------------------
 // Detached evaluation points for the current state, w_k = x - lambda*e_k
 // (Algorithm 1, "detach" line).  blockIdx.y is the worker, one thread per 4 columns.
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(DEF_THREADS) void def_detach_kernel(DefStepArgs a, int vec_xw)
+__global__ __launch_bounds__(DEF_THREADS) void def_detach_kernel(DefStepArgs a)
 {
     const uint64_t i = ((uint64_t)blockIdx.x * DEF_THREADS + threadIdx.x) * 4;
     if (i >= a.d) return;
+    const v4f xv = load_x_group(a, i);
     for (uint32_t k = blockIdx.y; k < a.W; k += gridDim.y) {
         const v4f ev = load4<true>(a.e + (uint64_t)k * a.ld + i);    // padded rows: always in bounds
-        float *w = a.w + (uint64_t)k * a.ldw;
-        if (vec_xw && i + 4 <= a.d) {
-            const v4f xv = load4<false>(a.x_flat + i);
-            v4f wv;
+        v4f wv;
 #pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                const float scaled = a.lam * ev[c];
-                wv[c] = xv[c] - scaled;
-            }
-            store4<true>(w + i, wv);
-        } else {
-#pragma unroll
-            for (int c = 0; c < 4; ++c)
-                if (i + c < a.d) {
-                    const float scaled = a.lam * ev[c];
-                    w[i + c] = *param_addr(a, i + c) - scaled;
-                }
+        for (int c = 0; c < 4; ++c) {
+            const float scaled = a.lam * ev[c];
+            wv[c] = xv[c] - scaled;
         }
+        store_group(a.w + (uint64_t)k * a.ldw, i, a.d, wv);
     }
 }
 
@@ -654,9 +668,7 @@ hipError_t def_launch_detach(const DefStepArgs &a, hipStream_t st)
     const uint64_t quads = (a.d + 3) / 4;
     const uint64_t blocks = (quads + DEF_THREADS - 1) / DEF_THREADS;
     if (blocks > 0x7fffffffull) return hipErrorInvalidConfiguration;
-    const int vec_xw = a.x_flat != nullptr && ((uintptr_t)a.x_flat % 16 == 0) &&
-                       ((uintptr_t)a.w % 16 == 0) && a.ldw % 4 == 0;
-    def_detach_kernel<<<dim3((uint32_t)blocks, a.W < 65535u ? a.W : 65535u), dim3(DEF_THREADS), 0, st>>>(a, vec_xw);
+    def_detach_kernel<<<dim3((uint32_t)blocks, a.W < 65535u ? a.W : 65535u), dim3(DEF_THREADS), 0, st>>>(a);
     return hipGetLastError();
 }
 
@@ -665,7 +677,6 @@ hipError_t def_launch_output(const DefStepArgs &a, float *y, hipStream_t st)
     const uint64_t quads = (a.d + 3) / 4;
     const uint64_t blocks = (quads + DEF_THREADS - 1) / DEF_THREADS;
     if (blocks > 0x7fffffffull) return hipErrorInvalidConfiguration;
-    const int vec_xy = a.x_flat != nullptr && ((uintptr_t)a.x_flat % 16 == 0) && ((uintptr_t)y % 16 == 0);
-    def_output_kernel<<<dim3((uint32_t)blocks), dim3(DEF_THREADS), 0, st>>>(a, y, vec_xy);
+    def_output_kernel<<<dim3((uint32_t)blocks), dim3(DEF_THREADS), 0, st>>>(a, y);
     return hipGetLastError();
 }
