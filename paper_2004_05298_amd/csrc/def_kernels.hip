@@ -403,23 +403,26 @@ __global__ __launch_bounds__(DEF_THREADS) void def_output_kernel(DefStepArgs a, 
 
 // ---------------------------------------------------------------------------
 // Detached evaluation points for the current state, w_k = x - lambda*e_k
-// (Algorithm 1, "detach" line).  blockIdx.y is the worker, one thread per 4 columns.
+// (Algorithm 1, "detach" line).  Same launch shape as the streaming pass: one wave
+// per (worker, 256 indices), blocked order so that x is served by L2 to all workers.
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(DEF_THREADS) void def_detach_kernel(DefStepArgs a)
+__global__ __launch_bounds__(DEF_VEC_THREADS) void def_detach_kernel(DefStepArgs a, uint64_t tiles,
+                                                                     uint64_t total)
 {
-    const uint64_t i = ((uint64_t)blockIdx.x * DEF_THREADS + threadIdx.x) * 4;
+    uint32_t k;
+    uint64_t tile;
+    if (!decode_item<MAP_BLOCKED>(total, tiles, a.W, DEF_SUPER_TILES, k, tile)) return;
+    const uint64_t i = tile * DEF_VEC_TILE + threadIdx.x * 4;
     if (i >= a.d) return;
     const v4f xv = load_x_group(a, i);
-    for (uint32_t k = blockIdx.y; k < a.W; k += gridDim.y) {
-        const v4f ev = load4<true>(a.e + (uint64_t)k * a.ld + i);    // padded rows: always in bounds
-        v4f wv;
+    const v4f ev = load4<true>(a.e + (uint64_t)k * a.ld + i);        // padded rows: always in bounds
+    v4f wv;
 #pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            const float scaled = a.lam * ev[c];
-            wv[c] = xv[c] - scaled;
-        }
-        store_group(a.w + (uint64_t)k * a.ldw, i, a.d, wv);
+    for (int c = 0; c < 4; ++c) {
+        const float scaled = a.lam * ev[c];
+        wv[c] = xv[c] - scaled;
     }
+    store_group(a.w + (uint64_t)k * a.ldw, i, a.d, wv);
 }
 
 // ---------------------------------------------------------------------------
@@ -665,10 +668,11 @@ hipError_t def_launch_diagnostics(const DefStepArgs &a, float lambda, double *pa
 
 hipError_t def_launch_detach(const DefStepArgs &a, hipStream_t st)
 {
-    const uint64_t quads = (a.d + 3) / 4;
-    const uint64_t blocks = (quads + DEF_THREADS - 1) / DEF_THREADS;
-    if (blocks > 0x7fffffffull) return hipErrorInvalidConfiguration;
-    def_detach_kernel<<<dim3((uint32_t)blocks, a.W < 65535u ? a.W : 65535u), dim3(DEF_THREADS), 0, st>>>(a);
+    static_assert(DEF_VEC_QUADS == 1, "def_detach_kernel handles one group per thread");
+    const uint64_t tiles = (a.d + DEF_VEC_TILE - 1) / DEF_VEC_TILE;
+    const uint64_t total = tiles * a.W;
+    if (total > 0x7fffffffull - 8) return hipErrorInvalidConfiguration;
+    def_detach_kernel<<<dim3(grid_for(total)), dim3(DEF_VEC_THREADS), DEF_VEC_LDS_RESERVE, st>>>(a, tiles, total);
     return hipGetLastError();
 }
 
