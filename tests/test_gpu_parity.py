@@ -272,11 +272,14 @@ def test_flat_gradients_with_tensor_params(dev):
 @pytest.mark.parametrize("d,W,R", [
     (1, 1, 1), (3, 2, 3), (4, 3, 1), (5, 1, 2), (63, 4, 63), (64, 2, 64), (257, 33, 5),
     (4096, 17, 4096), (4097, 16, 1), (8191, 3, 2), (16384, 1, 7), (12289, 40, 3),
+    (2000, 300, 7), (256, 2, 1), (512, 3, 2), (768, 5, 3),
 ])
 def test_degenerate_shapes(dev, d, W, R):
     base = wl.tiny()
     w = wl.shrunk(base, d=d, n_tensors=min(3, d), W=W, R=R, T=5, pool=3)
-    exact = run_case(dev, w, weight_decay=1e-3)
+    # steps 1 and 3: blocks that start exactly on a 256-index tile edge (if there is one)
+    edge = 256 if d > 256 else 0
+    exact = run_case(dev, w, weight_decay=1e-3, forced=lambda t: {1: edge, 3: (d - w.B) % d}.get(t))
     assert all(exact.values()), exact
 
 
