@@ -239,7 +239,6 @@ def main() -> int:
         torch.cuda.synchronize()
         elapsed = time.perf_counter() - t0
         kernel_ms = ctx.profile_end(args.steps)
-    vectorised = ctx.last_path_vectorised()
     kernel_name = ctx.last_kernel()
     aux = None
     if args.aux:
@@ -287,7 +286,7 @@ def main() -> int:
         "config": {"workload": w.name, "d": w.d, "W": w.W, "R": w.R, "B": w.B,
                    "n_tensors": w.n_tensors, "momentum": w.momentum,
                    "weight_decay": w.weight_decay, "lr": w.lr, "variant": variant, "detach_lambda": args.detach,
-                   "gradient_sets": w.pool, "inputs": "per-tensor pointers" if args.tensors else "flat", "launch": f"hip graph of {args.graph} steps" if args.graph else "eager", "path": "dwordx4" if vectorised else "dword",
+                   "gradient_sets": w.pool, "inputs": "per-tensor pointers" if args.tensors else "flat", "launch": f"hip graph of {args.graph} steps" if args.graph else "eager",
                    "algorithmic_bytes_per_step": ab["step"]},
         "roofline": {"bound": "hbm", "kernel": kernel_name,
                      "achieved": None if achieved is None else round(achieved, 2),

@@ -232,7 +232,7 @@ int def_state_ptrs(def_ctx *ctx, float **e, float **m, float **avg_block, uint64
 
 /* How the last step addressed its inputs: 1 = flat gradient buffer (and flat x if the pass
  * reads x), 0 = per-tensor pointers resolved through the offset table. */
-int def_last_path(const def_ctx *ctx, int *vectorised);
+int def_last_path(const def_ctx *ctx, int *flat);
 
 /*
  * Name and launch shape of the streaming kernel the last step ran, e.g.

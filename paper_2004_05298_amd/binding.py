@@ -248,7 +248,7 @@ class DefContext:
         _check(self._lib.def_last_block(self._h, ctypes.byref(s), ctypes.byref(n)), "def_last_block")
         return s.value, n.value
 
-    def last_path_vectorised(self) -> bool:
+    def last_path_flat(self) -> bool:
         v = ctypes.c_int()
         _check(self._lib.def_last_path(self._h, ctypes.byref(v)), "def_last_path")
         return bool(v.value)

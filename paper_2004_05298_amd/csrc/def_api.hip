@@ -67,7 +67,7 @@ struct def_ctx {
     int64_t forced = -1;
     uint64_t last_start = 0;
     bool has_last = false;
-    int last_vec = 0;
+    int last_flat = 0;
     hipStream_t stream = nullptr;
     // device state owned by the library
     float *e = nullptr, *m = nullptr, *msg = nullptr, *avg = nullptr;
@@ -154,7 +154,7 @@ int run_step(def_ctx *c, DefStepArgs &a, float *y_out)
     c->last_start = a.s;
     c->has_last = true;
     // 1: flat addressing; 0: gradients and/or the parameters the pass reads come through tables
-    c->last_vec = (a.g_ptrs || ((a.wd != 0.0f || a.w) && a.x_ptrs)) ? 0 : 1;
+    c->last_flat = (a.g_ptrs || ((a.wd != 0.0f || a.w) && a.x_ptrs)) ? 0 : 1;
     def_describe_stream_kernel(a, c->kernel_name, sizeof c->kernel_name);
     c->forced = -1;
     ++c->t;
@@ -472,10 +472,10 @@ int def_state_ptrs(def_ctx *ctx, float **e, float **m, float **avg_block, uint64
     return DEF_OK;
 }
 
-int def_last_path(const def_ctx *ctx, int *vectorised)
+int def_last_path(const def_ctx *ctx, int *flat)
 {
-    if (!ctx || !vectorised || !ctx->has_last) return DEF_EINVAL;
-    *vectorised = ctx->last_vec;
+    if (!ctx || !flat || !ctx->has_last) return DEF_EINVAL;
+    *flat = ctx->last_flat;
     return DEF_OK;
 }
 

@@ -9,7 +9,7 @@
 constexpr uint32_t DEF_GRAD_TABLES = 4;      // gradient pointer tables kept on the device
 constexpr uint32_t DEF_AVG_TILE = 256;      // block columns per workgroup of the averaging kernel
 constexpr uint32_t DEF_THREADS = 256;       // workgroup size of every kernel but the streaming pass
-// Launch shape of the vectorised streaming kernel.  Measured on MI355X (d = 25.6 M,
+// Launch shape of the streaming kernel.  Measured on MI355X (d = 25.6 M,
 // W = 16): one wave per workgroup with one float4 group per lane beats every larger
 // tile (64x1: 78 % of the 8 TB/s HBM peak, 256x1: 75 %, 256x4: 73 %); stores
 // in particular lose bandwidth when a wave issues several of them back to back.
@@ -22,7 +22,7 @@ constexpr uint32_t DEF_VEC_TILE = DEF_VEC_THREADS * DEF_VEC_QUADS * 4;   // indi
 // workers pass over it.  Measured (d = 25.6 M, W = 16, random data): 8192 -> 78.4 %,
 // 16384 -> 79.6 %, 32768 -> 75 % of the HBM peak (the piece no longer fits in L2).
 constexpr uint32_t DEF_SUPER_TILES = 16384;
-// Dynamic LDS reserved per one-wave workgroup of the vectorised kernel.  The kernel
+// Dynamic LDS reserved per one-wave workgroup of the streaming kernel.  The kernel
 // does not touch it: with 160 KiB of LDS per compute unit the reservation caps
 // residency at 16 workgroups (4 waves per SIMD).  Fewer waves in flight keep the
 // window of addresses being read and written narrower, which the memory system

@@ -32,7 +32,7 @@
 typedef float v4f __attribute__((ext_vector_type(4)));
 // The same four floats at any 4-byte aligned address.  The hardware accepts dwordx4
 // accesses at dword alignment, so caller-owned buffers (gradients, x, w) need not be
-// 16-byte aligned for the vectorised kernel; the library's own rows always are.
+// 16-byte aligned; the library's own rows always are.
 typedef v4f v4f_u __attribute__((aligned(4)));
 
 namespace {

@@ -122,7 +122,7 @@ def test_gpu_closed_loop_reproduces_oracle(name, mu):
             gv.add_(noise[t % prob.pool])
             ctx.step(g, ld, y if t == T - 1 else None)
         torch.cuda.synchronize()
-        assert ctx.last_path_vectorised()
+        assert ctx.last_path_flat()
         e, m, _ = ctx.state_tensors()
         xg, yg = x.cpu().numpy(), y.cpu().numpy()
         assert np.array_equal(xg.view(np.uint32), ora.x.view(np.uint32))

@@ -1,6 +1,5 @@
 """GPU parity at the full sizes of the model-shaped configurations, in the launch
-configuration the benchmark times (flat gradients, padded row stride, vectorised
-kernel).
+configuration the benchmark times (flat gradients, padded row stride).
 
 The two smaller configurations are compared buffer for buffer with the plain C
 oracle.  For the two largest, the oracle simulates a sample of columns exactly
@@ -73,7 +72,7 @@ def test_whole_buffers_against_c_oracle(dev, name):
             s = ora.step(host_pool[t % w.pool], start=start)
             assert ctx.last_block() == (s, w.B)
         torch.cuda.synchronize()
-        assert ctx.last_path_vectorised()
+        assert ctx.last_path_flat()
         e, m, avg = ctx.state_tensors()
         e, m, avg = e.cpu().numpy(), m.cpu().numpy(), avg.cpu().numpy()
         xg = x.cpu().numpy()
@@ -145,7 +144,7 @@ def test_sampled_columns_at_full_size(dev, name):
             s = ora.step(host_cols[t % w.pool], start=start)
             assert ctx.last_block() == (s, w.B) and s == starts[t]
         torch.cuda.synchronize()
-        assert ctx.last_path_vectorised()
+        assert ctx.last_path_flat()
         e, m, avg = ctx.state_tensors()
         xg = x.index_select(0, cols_dev).cpu().numpy()
         eg = e.index_select(1, cols_dev).cpu().numpy()

@@ -162,9 +162,9 @@ def run_case(dev, w, *, weight_decay=None, momentum=None, T=None, flat_params=Tr
         torch.cuda.synchronize()
         if mode == "flat":
             reads_x = wd != 0 or detach is not None
-            assert ctx.last_path_vectorised() == (flat_params or not reads_x)
+            assert ctx.last_path_flat() == (flat_params or not reads_x)
         else:
-            assert not ctx.last_path_vectorised()
+            assert not ctx.last_path_flat()
         e, m, _ = fetch_state(ctx, W, d)
         if flat_params:
             x = x_dev.cpu().numpy()
