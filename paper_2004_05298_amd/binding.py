@@ -209,7 +209,7 @@ class DefContext:
         _check(self._lib.def_output(self._h, _ptr(y_out)), "def_output")
 
     def set_detach(self, w_out, ldw: int = 0, lam: float = 0.0) -> None:
-        self._keep.append(w_out)
+        self._detach_out = w_out                      # keep the tensor alive while it is set
         _check(self._lib.def_set_detach(self._h, _ptr(w_out), ldw, lam), "def_set_detach")
 
     def detach(self, w_out, ldw: int, lam: float) -> None:

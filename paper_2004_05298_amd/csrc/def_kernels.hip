@@ -93,34 +93,27 @@ __device__ __forceinline__ uint64_t block_start_of(const DefStepArgs &a)
 }
 
 // Workgroup ids are dealt round-robin to the 8 XCDs.  Work items (one worker's
-// piece of one column tile) are numbered 0..tiles*W-1; MAP chooses how a
-// workgroup id becomes a work item:
-//   MAP_LINEAR_T  item = workgroup id, tile index fastest: each worker row is
-//               streamed front to back, one row after the other;
-//   MAP_LINEAR_K  item = workgroup id, worker index fastest;
-//   MAP_XCD_T / MAP_XCD_K  as above, but XCD c owns the contiguous item range
-//               [c*n/8, (c+1)*n/8);
-//   MAP_BLOCKED   the columns are cut into super-tiles of DEF_SUPER_TILES tiles;
-//               within a super-tile the workers follow one another, each
-//               streaming its piece of the super-tile front to back.  With
-//               weight decay all W workers read the same piece of x within a
-//               short time, so it is fetched from HBM once and then served by L2;
-//   MAP_XCD_BLOCKED  MAP_BLOCKED with XCD-contiguous item ranges.
-enum { MAP_XCD_K = 0, MAP_LINEAR_K = 1, MAP_LINEAR_T = 2, MAP_XCD_T = 3, MAP_BLOCKED = 4,
-       MAP_XCD_BLOCKED = 5 };
+// piece of one column tile) are numbered 0..tiles*W-1 and workgroup b takes item b;
+// MAP chooses what item b is:
+//   MAP_LINEAR_T  tile index fastest: each worker row is streamed front to back,
+//               one row after the other;
+//   MAP_BLOCKED   the columns are cut into super-tiles of `super` tiles; within a
+//               super-tile the workers follow one another, each streaming its
+//               piece of the super-tile front to back.  When every worker reads x
+//               (weight decay, detached points) all W of them pass over the same
+//               piece of x within a short time, so it is fetched from HBM once and
+//               then served by the L2 of each XCD.
+// (Worker index fastest and XCD-contiguous item ranges were measured too and were
+// 3 to 15 % slower: hopping between W rows per tile costs more than it saves.)
+enum { MAP_LINEAR_T = 2, MAP_BLOCKED = 4 };
 
 template <int MAP>
 __device__ __forceinline__ bool decode_item(uint64_t total, uint64_t tiles, uint32_t W, uint32_t super,
                                             uint32_t &k, uint64_t &tile)
 {
-    uint64_t item = blockIdx.x;
-    if constexpr (MAP == MAP_XCD_K || MAP == MAP_XCD_T || MAP == MAP_XCD_BLOCKED)
-        item = (uint64_t)(blockIdx.x & 7u) * (uint64_t)(gridDim.x >> 3) + (uint64_t)(blockIdx.x >> 3);
+    const uint64_t item = blockIdx.x;
     if (item >= total) return false;
-    if constexpr (MAP == MAP_XCD_K || MAP == MAP_LINEAR_K) {
-        k = (uint32_t)(item % W);
-        tile = item / W;
-    } else if constexpr (MAP == MAP_LINEAR_T || MAP == MAP_XCD_T) {
+    if constexpr (MAP == MAP_LINEAR_T) {
         tile = item % tiles;
         k = (uint32_t)(item / tiles);
     } else {
@@ -541,7 +534,7 @@ __global__ void def_ctl_set_kernel(DefCtl *ctl, uint32_t mask, uint64_t t, uint6
 
 uint32_t grid_for(uint64_t total)
 {
-    return (uint32_t)((total + 7) / 8 * 8);                   // the XCD maps need a multiple of 8
+    return (uint32_t)((total + 7) / 8 * 8);                   // whole rounds over the 8 XCDs
 }
 
 }  // namespace
