@@ -109,6 +109,9 @@ MUTANTS = [
     ("detach ignores lambda", "out[k] = self.x - lam * self.e[k]", "out[k] = self.x - self.e[k]"),
     ("detach uses momentum", "out[k] = self.x - lam * self.e[k]", "out[k] = self.x - lam * self.m[k]"),
     ("detach uses worker 0", "out[k] = self.x - lam * self.e[k]", "out[k] = self.x - lam * self.e[0]"),
+    ("compact block starts one late",
+     "j = (np.int64(self.last_start) + np.arange(self.B, dtype=np.int64)) % np.int64(self.d)",
+     "j = (np.int64(self.last_start) + 1 + np.arange(self.B, dtype=np.int64)) % np.int64(self.d)"),
     ("diagnostics: mean error not divided", "e_bar = acc / np.float64(self.W)", "e_bar = acc"),
     ("diagnostics: mean_sq is a sum", "for k in range(self.W)) / self.W)\n        dist", "for k in range(self.W)))\n        dist"),
     ("diagnostics: lambda* inverted", "lam_star=(bar_sq / mean_sq if", "lam_star=(mean_sq / bar_sq if"),

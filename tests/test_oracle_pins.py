@@ -432,6 +432,9 @@ def test_age_counter_closed_form(kind, d, R, W):
         s = o.step(ones, start=forced)
         assert s == (forced if forced is not None else block_start(123, t, d))
         kept = {(s + j) % d for j in range(B)}
+        # the averaged block in compact order: entry j belongs to index (s+j) mod d and
+        # is 1 + the age that index had before this step
+        assert [int(v) for v in np.asarray(o.compact_block())] == [age[(s + j) % d] + 1 for j in range(B)]
         for i in range(d):
             if i in kept:
                 xs[i] -= age[i] + 1
