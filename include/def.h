@@ -21,7 +21,10 @@
  *     rounded separately (no fused multiply-add), so results do not depend on
  *     the launch shape.
  *   - "DEVICE" pointers are HIP device memory on the GPU that was current when
- *     def_init was called; "HOST" pointers are ordinary process memory.
+ *     def_init was called (the stream must belong to it too); "HOST" pointers
+ *     are ordinary process memory.  Later calls make that GPU current while
+ *     they run and put the caller's back before they return, so a process that
+ *     drives several GPUs need not switch devices around calls into a context.
  *   - Every function returns DEF_OK (0) or a negative def_status.  No function
  *     throws or aborts.  A call that returns DEF_EINVAL has changed nothing.
  *   - def_step / def_a_step / def_output only enqueue work on the context's

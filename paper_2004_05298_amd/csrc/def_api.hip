@@ -57,6 +57,36 @@ uint64_t draw_start(uint64_t seed, uint64_t t, uint64_t d)
 
 uint64_t round_up(uint64_t v, uint64_t to) { return (v + to - 1) / to * to; }
 
+// Makes one GPU current for the duration of a call and puts the caller's back afterwards.
+class DeviceScope {
+public:
+    explicit DeviceScope(int device)
+    {
+        err_ = hipGetDevice(&prev_);
+        if (err_ == hipSuccess && prev_ != device) {
+            err_ = hipSetDevice(device);
+            switched_ = err_ == hipSuccess;
+        }
+    }
+    ~DeviceScope()
+    {
+        if (switched_) (void)hipSetDevice(prev_);
+    }
+    DeviceScope(const DeviceScope &) = delete;
+    DeviceScope &operator=(const DeviceScope &) = delete;
+    hipError_t status() const { return err_; }
+
+private:
+    int prev_ = -1;
+    bool switched_ = false;
+    hipError_t err_ = hipSuccess;
+};
+
+// Every entry point that reaches the HIP runtime runs on the GPU the context was made on.
+#define DEF_ON_DEVICE(c)                                              \
+    DeviceScope scope__((c)->device);                                 \
+    if (scope__.status() != hipSuccess) return hip_fail(scope__.status())
+
 }  // namespace
 
 struct def_ctx {
@@ -69,6 +99,7 @@ struct def_ctx {
     bool has_last = false;
     int last_flat = 0;
     hipStream_t stream = nullptr;
+    int device = 0;           // GPU that was current in def_init; owns the stream and all buffers
     // device state owned by the library
     float *e = nullptr, *m = nullptr, *msg = nullptr, *avg = nullptr;
     double *diag = nullptr;   // per-workgroup partial sums of def_diagnostics
@@ -214,6 +245,10 @@ int def_init(def_ctx **out, const def_config *cfg)
     c->lr = cfg->lr; c->mu = cfg->momentum; c->wd = cfg->weight_decay;
     c->seed = cfg->seed;
     c->stream = (hipStream_t)cfg->stream;
+    {
+        const hipError_t err = hipGetDevice(&c->device);
+        if (err != hipSuccess) { delete c; return hip_fail(err); }
+    }
     c->x_flat = cfg->params;
     c->ld = round_up(c->d, 64);
     c->ldmsg = round_up(c->B, DEF_AVG_TILE);
@@ -277,7 +312,9 @@ int def_init(def_ctx **out, const def_config *cfg)
 int def_destroy(def_ctx *ctx)
 {
     if (!ctx) return DEF_EINVAL;
-    const hipError_t err = hipStreamSynchronize(ctx->stream);
+    DeviceScope scope(ctx->device);
+    hipError_t err = scope.status();
+    if (err == hipSuccess) err = hipStreamSynchronize(ctx->stream);
     free_ctx(ctx);
     return err == hipSuccess ? DEF_OK : hip_fail(err);
 }
@@ -286,6 +323,7 @@ int def_step(def_ctx *ctx, const float *grads, uint64_t ld, float *y_out)
 {
     if (!ctx || !grads || ld < ctx->d || (uintptr_t)grads % 4 != 0) return DEF_EINVAL;
     if (y_out && (uintptr_t)y_out % 4 != 0) return DEF_EINVAL;
+    DEF_ON_DEVICE(ctx);
     DefStepArgs a = base_args(ctx, next_start(ctx));
     a.g_flat = grads;
     a.ldg = ld;
@@ -305,6 +343,7 @@ int def_step_tensors(def_ctx *ctx, const float *const *grad_ptrs, float *y_out)
     const size_t n = (size_t)ctx->W * ctx->L;
     for (size_t q = 0; q < n; ++q)
         if (!grad_ptrs[q] || (uintptr_t)grad_ptrs[q] % 4 != 0) return DEF_EINVAL;
+    DEF_ON_DEVICE(ctx);
     def_ctx::GradTable *use = nullptr, *free_slot = nullptr, *oldest = nullptr;
     for (auto &tb : ctx->gtab) {
         if (!tb.dev) {
@@ -350,6 +389,7 @@ int def_a_step_tensors(def_ctx *ctx, const float *const *grad_ptrs)
 int def_output(def_ctx *ctx, float *y_out)
 {
     if (!ctx || !y_out || (uintptr_t)y_out % 4 != 0) return DEF_EINVAL;
+    DEF_ON_DEVICE(ctx);
     DefStepArgs a = base_args(ctx, 0);
     DEF_HIP(def_launch_output(a, y_out, ctx->stream));
     return DEF_OK;
@@ -373,6 +413,7 @@ int def_detach(def_ctx *ctx, float *w_out, uint64_t ldw, float lambda)
     if (!ctx || !w_out || (uintptr_t)w_out % 4 != 0 || ldw < ctx->d ||
         !(lambda >= 0.0f && lambda <= 1.0f))
         return DEF_EINVAL;
+    DEF_ON_DEVICE(ctx);
     DefStepArgs a = base_args(ctx, 0);
     a.w = w_out; a.ldw = ldw; a.lam = lambda;
     DEF_HIP(def_launch_detach(a, ctx->stream));
@@ -382,6 +423,7 @@ int def_detach(def_ctx *ctx, float *w_out, uint64_t ldw, float lambda)
 int def_diagnostics(def_ctx *ctx, float lambda, double *out)
 {
     if (!ctx || !out || (uintptr_t)out % 8 != 0 || !(lambda >= 0.0f && lambda <= 1.0f)) return DEF_EINVAL;
+    DEF_ON_DEVICE(ctx);
     DefStepArgs a = base_args(ctx, 0);
     DEF_HIP(def_launch_diagnostics(a, lambda, ctx->diag, out, ctx->stream));
     return DEF_OK;
@@ -390,6 +432,7 @@ int def_diagnostics(def_ctx *ctx, float lambda, double *out)
 int def_set_seed(def_ctx *ctx, uint64_t seed)
 {
     if (!ctx) return DEF_EINVAL;
+    DEF_ON_DEVICE(ctx);
     if (ctx->device_draw)
         DEF_HIP(def_launch_ctl_set(ctx->ctl, DEF_CTL_SEED, 0, seed, -1, ctx->stream));
     ctx->seed = seed;
@@ -399,6 +442,7 @@ int def_set_seed(def_ctx *ctx, uint64_t seed)
 int def_set_device_draw(def_ctx *ctx, int on)
 {
     if (!ctx) return DEF_EINVAL;
+    DEF_ON_DEVICE(ctx);
     if (on && !ctx->device_draw)
         DEF_HIP(def_launch_ctl_set(ctx->ctl, DEF_CTL_T | DEF_CTL_SEED | DEF_CTL_FORCED, ctx->t, ctx->seed,
                                    ctx->forced, ctx->stream));
@@ -410,6 +454,7 @@ int def_sync_step(def_ctx *ctx)
 {
     if (!ctx) return DEF_EINVAL;
     if (!ctx->device_draw) return DEF_OK;
+    DEF_ON_DEVICE(ctx);
     DefCtl host;
     DEF_HIP(hipMemcpyAsync(&host, ctx->ctl, sizeof host, hipMemcpyDeviceToHost, ctx->stream));
     DEF_HIP(hipStreamSynchronize(ctx->stream));
@@ -432,6 +477,7 @@ int def_set_lr(def_ctx *ctx, float lr)
 int def_set_step(def_ctx *ctx, uint64_t t)
 {
     if (!ctx) return DEF_EINVAL;
+    DEF_ON_DEVICE(ctx);
     if (ctx->device_draw) DEF_HIP(def_launch_ctl_set(ctx->ctl, DEF_CTL_T, t, 0, -1, ctx->stream));
     ctx->t = t;
     return DEF_OK;
@@ -448,6 +494,7 @@ int def_force_next_start(def_ctx *ctx, int64_t s)
 {
     if (!ctx) return DEF_EINVAL;
     if (s >= 0 && (uint64_t)s >= ctx->d) return DEF_EINVAL;
+    DEF_ON_DEVICE(ctx);
     if (ctx->device_draw)
         DEF_HIP(def_launch_ctl_set(ctx->ctl, DEF_CTL_FORCED, 0, 0, s < 0 ? -1 : s, ctx->stream));
     ctx->forced = s < 0 ? -1 : s;
@@ -487,6 +534,7 @@ const char *def_last_kernel(const def_ctx *ctx)
 int def_profile_begin(def_ctx *ctx, uint32_t max_steps)
 {
     if (!ctx || max_steps == 0 || max_steps > (1u << 20)) return DEF_EINVAL;
+    DEF_ON_DEVICE(ctx);
     for (hipEvent_t ev : ctx->ev) (void)hipEventDestroy(ev);
     ctx->ev.clear();
     ctx->prof_cap = ctx->prof_n = 0;
@@ -507,6 +555,7 @@ int def_profile_begin(def_ctx *ctx, uint32_t max_steps)
 int def_profile_end(def_ctx *ctx, float *ms, uint32_t cap, uint32_t *n)
 {
     if (!ctx || !n || (cap && !ms)) return DEF_EINVAL;
+    DEF_ON_DEVICE(ctx);
     const uint32_t recorded = ctx->prof_n;
     int rc = DEF_OK;
     if (recorded) {
