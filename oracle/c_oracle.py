@@ -82,6 +82,10 @@ class DefOracleC:
     def threads(self) -> int:
         return int(self._lib.def_oracle_threads())
 
+    def set_threads(self, threads: int) -> None:
+        """OpenMP threads the C routines use from now on (process-wide)."""
+        self._lib.def_oracle_set_threads(int(threads))
+
     def set_lr(self, lr: float) -> None:
         self.lr = np.float32(lr)
 
