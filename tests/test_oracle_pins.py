@@ -391,6 +391,52 @@ def test_diagnostics_against_norms_of_detached_points(dtype):
     assert fresh == dict(bar_sq=0.0, mean_sq=0.0, lam_star=0.0, dist=0.0)
 
 
+def test_error_memory_stationary_moments_and_bounds():
+    """Gradients g_k = c + noise_k that do not depend on x (mu = 0): an index that
+    was last kept `a` steps ago holds e_k = eta*(a*c + sum of a noise terms).  With
+    uniform circular starts every index is kept with probability delta = B/d
+    independently per step (Assumption 5 with equality), so the age is geometric,
+    E[a] = (1-delta)/delta and E[a^2] = (1-delta)(2-delta)/delta^2, which gives
+      E (1/K) sum_k ||e_k||^2        = eta^2 [sigma^2 E[a] + M^2 E[a^2]]
+      E (1/K) sum_k ||e_t - lam e_k||^2 = eta^2 [B1 sigma^2 E[a] + (1-lam)^2 M^2 E[a^2]]
+    with sigma^2 = E||noise||^2, M^2 = ||c||^2, B1 = (1/K - lam)^2 + (K-1)/K^2 (the
+    constant of Lemma A.2).  Time averages over a long run are checked against these
+    values, and against the upper bounds of Lemma A.3 and Lemma A.2 (Appendix A)."""
+    d, W, R, eta, T, burn = 240, 4, 8, 0.1, 6000, 300
+    delta = block_length(d, R) / d
+    rng = np.random.default_rng(20)
+    c = rng.standard_normal(d) * 0.05
+    sig_g = 0.2
+    M2, sigma2 = float(c @ c), d * sig_g ** 2
+    Ea, Ea2 = (1 - delta) / delta, (1 - delta) * (2 - delta) / delta ** 2
+    lams = (0.0, 0.3, 1.0)
+    o = DefOracle(np.zeros(d), W, R, eta, 0.0, 0.0, 77, dtype=np.float64)
+    acc = {lam: [] for lam in lams}
+    mean_sq, bar_sq = [], []
+    for t in range(T):
+        o.step(c[None, :] + sig_g * rng.standard_normal((W, d)))
+        if t >= burn:
+            for lam in lams:
+                acc[lam].append(o.diagnostics(lam)["dist"])
+            dg = o.diagnostics(0.0)
+            mean_sq.append(dg["mean_sq"])
+            bar_sq.append(dg["bar_sq"])
+    want_mean = eta ** 2 * (sigma2 * Ea + M2 * Ea2)
+    assert np.mean(mean_sq) == pytest.approx(want_mean, rel=0.04)
+    # Lemma A.3: (1/K) sum_k E||e_k||^2 <= eta^2 (sigma^2 + M^2) / (sqrt(1/(1-delta)) - 1)^2
+    assert np.mean(mean_sq) <= eta ** 2 * (sigma2 + M2) / (np.sqrt(1 / (1 - delta)) - 1) ** 2
+    for lam in lams:
+        B1 = (1.0 / W - lam) ** 2 + (W - 1) / W ** 2
+        want = eta ** 2 * (B1 * sigma2 * Ea + (1 - lam) ** 2 * M2 * Ea2)
+        assert np.mean(acc[lam]) == pytest.approx(want, rel=0.04), lam
+        # Lemma A.2 with L = 0
+        cap = eta ** 2 * (B1 * sigma2 + 2 * (1 - lam) ** 2 * M2) / \
+            (np.sqrt((1 - delta / 2) / (1 - delta)) - 1) ** 2
+        assert np.mean(acc[lam]) <= cap, lam
+    # lambda = 0 is error feedback: the distance is ||e_t||^2 itself
+    assert np.mean(acc[0.0]) == pytest.approx(np.mean(bar_sq), rel=1e-12)
+
+
 @pytest.mark.parametrize("kind,tol", [("np64", 1e-12), ("np32", 2e-5), ("c32", 2e-5)])
 def test_closed_loop_single_worker_follows_gradient_descent(kind, tol):
     """K = 1, lambda = 1 on f(theta) = 0.5*||theta - c||^2 with the gradient taken at
