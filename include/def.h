@@ -57,7 +57,7 @@ typedef struct def_config {
     uint32_t W;             /* number of workers (the paper's K), >= 1; W * ceil(d/256) must be
                                below 2^31 (one workgroup per worker and 256 indices)            */
     uint32_t R;             /* compression ratio, integer, 1 <= R <= d.  The kept block has
-                               B = ceil(d/R) elements (delta = B/d, Assumption 5).              */
+                               B = ceil(d/R) elements (delta = B/d, Assumption 4.2).            */
     float lr;               /* learning rate eta                                                */
     float momentum;         /* mu.  0 selects Algorithm 1 as printed: p = eta*g + e, and no
                                momentum buffer is allocated.                                    */
@@ -196,7 +196,7 @@ int def_set_seed(def_ctx *ctx, uint64_t seed);
 int def_set_device_draw(def_ctx *ctx, int on);
 int def_sync_step(def_ctx *ctx);
 
-/* Learning-rate schedules (eta_t in Theorem 1; step decay in Sec. 5 "Settings"). */
+/* Learning-rate schedules (eta = c/(t+1) in Theorem 4.6; step decay in Sec. 5 "Settings"). */
 int def_set_lr(def_ctx *ctx, float lr);
 
 /* Step counter, for resuming: the state of a run is (x, e, m, seed, t, eta). */

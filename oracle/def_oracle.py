@@ -48,8 +48,9 @@ from .philox import block_start
 
 
 def block_length(d: int, R: int) -> int:
-    """B = ceil(d / R) for an integer compression ratio R (Sec. 4, Assumption 5:
-    delta equals the kept fraction; Tables 1-2 use integer ratios)."""
+    """B = ceil(d / R) for an integer compression ratio R (Sec. 4, Assumption 4.2,
+    the delta-approximate compressor: delta equals the kept fraction; Tables 1-2
+    use integer ratios)."""
     if R < 1 or R > d:
         raise ValueError("need 1 <= R <= d")
     return -(-d // R)

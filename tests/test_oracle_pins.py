@@ -103,13 +103,13 @@ def test_start_is_pure_function_of_seed_and_step(kind):
 
 
 # --------------------------------------------------------------------------- #
-# Compressor properties: Assumption 3 (linearity), Assumption 5 and the remark
-# E_C[C(D)] = delta*D after Theorem 3 (RBGS keeps a fraction delta = B/d).
+# Compressor properties: Assumption 3.3 (linearity), Assumption 4.2 (delta-approximate
+# compressor) and Remark 4.11, E_C[C(D)] = delta*D (RBGS keeps a fraction delta = B/d).
 # --------------------------------------------------------------------------- #
 def test_block_length_is_the_ceiling():
     """Reading of "a block" for an integer ratio R that does not divide d:
     B = ceil(d/R), the smallest block whose kept fraction B/d is at least 1/R
-    (Assumption 5: delta is the compression ratio).  The five listed values are
+    (Assumption 4.2: delta is the compression ratio).  The five listed values are
     the block lengths of the five workload configurations."""
     for d, R, B in [(65536, 16, 4096), (853018, 32, 26657), (11689512, 64, 182649),
                     (25557032, 128, 199665), (138357544, 256, 540460)]:
@@ -195,7 +195,7 @@ def test_split_is_exact_and_block_is_literal_zero(kind):
 
 @pytest.mark.parametrize("kind", ["np64"])
 def test_allreduce_compatibility_whole_iteration(kind):
-    """P5: C is linear (Assumption 3), so W workers fed g_k and one worker fed
+    """P5: C is linear (Assumption 3.3), so W workers fed g_k and one worker fed
     mean_k g_k produce the same x path, and the single worker's error memory is
     the mean of the W error memories (mu and wd included: both are linear)."""
     d, W, R, T = 40, 4, 6, 15
@@ -395,7 +395,7 @@ def test_error_memory_stationary_moments_and_bounds():
     """Gradients g_k = c + noise_k that do not depend on x (mu = 0): an index that
     was last kept `a` steps ago holds e_k = eta*(a*c + sum of a noise terms).  With
     uniform circular starts every index is kept with probability delta = B/d
-    independently per step (Assumption 5 with equality), so the age is geometric,
+    independently per step (Assumption 4.2 with equality), so the age is geometric,
     E[a] = (1-delta)/delta and E[a^2] = (1-delta)(2-delta)/delta^2, which gives
       E (1/K) sum_k ||e_k||^2        = eta^2 [sigma^2 E[a] + M^2 E[a^2]]
       E (1/K) sum_k ||e_t - lam e_k||^2 = eta^2 [B1 sigma^2 E[a] + (1-lam)^2 M^2 E[a^2]]
