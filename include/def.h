@@ -7,7 +7,7 @@
  * iteration t of Algorithm 1 for all W (the paper's K) data-parallel workers,
  * whose gradients, error memories and momentum buffers all live on this GPU:
  *
- *   m_k <- mu*m_k + g_k                       Sec. 3.2 "Momentum Variant"
+ *   m_k <- mu*m_k + g_k                       Sec. 3.2 "Momentum Variant", Eq. (11)
  *   p_k  = eta*m_k + e_k                      Algorithm 1, error-feedback line
  *   e_k <- p_k - C(p_k)                       Algorithm 1, residual line
  *   C(p) = (1/W) sum_k C(p_k)                 Algorithm 1, ring-allreduce line
@@ -97,7 +97,7 @@ int def_destroy(def_ctx *ctx);
  *          are fastest.
  *   y_out  DEVICE or NULL.  If not NULL, d floats receive DEF's output
  *          y_{t+1} = x_{t+1} - (1/W) sum_k e_{k,t+1}   (Algorithm 1 "Output";
- *          Sec. 3.2, Eq. "y update").  The paper needs y only when the model is
+ *          Sec. 3.2, Eq. (8)).  The paper needs y only when the model is
  *          evaluated, so pass NULL in the training loop.
  * Draws s_t = def_block_start(seed, t, d) (or the forced start), keeps the
  * circular block {(s_t + j) mod d : 0 <= j < B}, then t <- t+1.
@@ -152,7 +152,7 @@ int def_detach(def_ctx *ctx, float *w_out, uint64_t ldw, float lambda);
 
 /*
  * Error-memory statistics of the current state (Sec. 3.2, items (1)-(3) and
- * Eq. "min d"; Appendix A, first display), accumulated in float64.  With
+ * Eq. (9); Appendix A, first display), accumulated in float64.  With
  * e_t = (1/W) sum_k e_k:
  *   out[0] = ||e_t||^2                       the distance ||x_t - y_t||^2 of plain EF
  *   out[1] = (1/W) sum_k ||e_k||^2

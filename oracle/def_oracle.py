@@ -9,9 +9,9 @@ What it follows (arXiv 2004.05298):
 * Algorithm 1 ("Detached Error Feedback"), the error-feedback, residual,
   all-reduce and update lines:  p_k = eta*g_k + e_k ;  e_k <- p_k - C(p_k) ;
   C(p) = (1/K) sum_k C(p_k) ;  x <- x - C(p).
-* Sec. 3.2 "Momentum Variant":  m_k <- mu*m_k + g_k ;  p_k = eta*m_k + e_k,
+* Sec. 3.2 "Momentum Variant", Eq. (11):  m_k <- mu*m_k + g_k ;  p_k = eta*m_k + e_k,
   with m_{k,0} = 0.
-* Algorithm 1 "Output" / Sec. 3.2 Eq. "y update":  y = x - (1/K) sum_k e_k for
+* Algorithm 1 "Output" / Sec. 3.2 Eq. (8):  y = x - (1/K) sum_k e_k for
   DEF, x itself for DEF-A.  DEF and DEF-A run the same iteration.
 * Algorithm 1, "detach" line:  worker k evaluates its next gradient at
   x - lambda*e_k  (`detached_points`).
@@ -174,7 +174,7 @@ class DefOracle:
           bar_sq   = ||e_t||^2                      (EF's distance ||x_t - y_t||^2)
           mean_sq  = (1/K) sum_k ||e_k||^2
           lam_star = bar_sq / mean_sq               (lambda*(t), Sec. 3.2 item (2))
-          dist     = (1/K) sum_k ||e_t - lam*e_k||^2   (Eq. "min d"), summed directly."""
+          dist     = (1/K) sum_k ||e_t - lam*e_k||^2   (Eq. (9)), summed directly."""
         e = self.e.astype(np.float64)
         acc = np.zeros(e.shape[1], dtype=np.float64)
         for k in range(self.W):

@@ -238,7 +238,7 @@ def test_ratio_one_is_momentum_sgd(kind, tol, mu, wd):
 
 
 # --------------------------------------------------------------------------- #
-# Trajectory identity y_{t+1} = y_t - eta*g_t (Sec. 3.2, Eq. "y update";
+# Trajectory identity y_{t+1} = y_t - eta*g_t (Sec. 3.2, Eq. (8);
 # Appendix A, main proof, first display), momentum form.
 # --------------------------------------------------------------------------- #
 @pytest.mark.parametrize("kind,tol", [("np64", 1e-12), ("np32", 3e-5), ("c32", 3e-5)])
@@ -265,7 +265,7 @@ def test_y_follows_uncompressed_momentum_path(kind, tol, d, W, R):
 
 # --------------------------------------------------------------------------- #
 # Single worker: Lemma C.1 (Appendix C) and the iterate-averaging special case
-# (Sec. 3.2 "DEF-A", Eq. "special sgd-ia"; Appendix C first displays).
+# (Sec. 3.2 "DEF-A", Eq. (12); Appendix C first displays).
 # --------------------------------------------------------------------------- #
 def test_single_worker_lemma_x_chases_sgd_path():
     """P7a: for K=1, x_{t+1} = x_t + C_t(y_{t+1} - x_t) with {y_t} the plain SGD
@@ -314,7 +314,7 @@ def test_scaling_compressor_gives_iterate_averaging():
 @pytest.mark.parametrize("kind", KINDS)
 def test_detached_points_special_cases(kind):
     """lambda = 0 is plain error feedback (gradient at x); K = 1 with lambda = 1
-    evaluates at y = x - e, the SGD path (Sec. 3.2, text after Eq. "y update")."""
+    evaluates at y = x - e, the SGD path (Sec. 3.2, text after Eq. (8))."""
     d, R, T = 41, 6, 9
     rng = np.random.default_rng(91)
     many = make(kind, rng.standard_normal(d), 3, R, 0.2, 0.9, 0.0, seed=12)
@@ -333,7 +333,7 @@ def test_detached_points_special_cases(kind):
 def test_detached_points_distance_identity():
     """(1/K) sum_k ||w_k - y||^2 = (1/K) sum_k ||e_t - lambda e_k||^2
     = lambda^2 * mean_k||e_k||^2 - 2 lambda ||e_t||^2 + ||e_t||^2  with e_t the mean
-    error (Sec. 3.2, Eq. "min d"; Appendix A, first display), and lambda*(t) =
+    error (Sec. 3.2, Eq. (9); Appendix A, first display), and lambda*(t) =
     ||e_t||^2 / mean_k||e_k||^2 minimises it."""
     d, W, R, T = 60, 5, 7, 14
     rng = np.random.default_rng(92)
