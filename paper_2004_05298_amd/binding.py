@@ -147,6 +147,14 @@ class DefContext:
         cfg.lr, cfg.momentum, cfg.weight_decay = lr, momentum, weight_decay
         cfg.seed = seed
         self._keep: List[object] = [params, param_tensors]
+        # the C side reads n_tensors+1 offsets and n_tensors pointers: lengths are checked here
+        n_tensors = 1 if tensor_offsets is None else len(tensor_offsets) - 1
+        if n_tensors < 1:
+            raise ValueError("tensor_offsets needs at least two entries")
+        if param_tensors is not None and len(param_tensors) != n_tensors:
+            raise ValueError(f"param_tensors has {len(param_tensors)} entries for {n_tensors} tensors")
+        if params is None and param_tensors is None:
+            raise ValueError("give params (one flat vector) or param_tensors")
         if tensor_offsets is not None:
             arr = (_u64 * len(tensor_offsets))(*[int(v) for v in tensor_offsets])
             cfg.tensor_offsets = ctypes.cast(arr, ctypes.POINTER(_u64))
@@ -192,6 +200,8 @@ class DefContext:
 
     def _gtable(self, grad_tensors):
         flat = [_ptr(g) for g in grad_tensors]
+        if len(flat) != self.W * self.n_tensors:      # the C side reads exactly W*n_tensors entries
+            raise ValueError(f"{len(flat)} gradient tensors given, W*n_tensors = {self.W * self.n_tensors}")
         return (_vp * len(flat))(*flat)
 
     def step_tensors(self, grad_tensors: Sequence, y_out=None) -> None:

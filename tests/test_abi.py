@@ -120,3 +120,20 @@ def test_init_rejects_problems_whose_grid_would_not_fit(lib):
     h = ctypes.c_void_p()
     assert lib.def_init(ctypes.byref(h), ctypes.byref(_cfg(d=2**39, W=64))) == binding.DEF_EINVAL
     assert not h.value
+
+
+def test_binding_checks_table_lengths_before_calling_the_library(lib):
+    """The C side reads n_tensors+1 offsets, n_tensors parameter pointers and
+    W*n_tensors gradient pointers from host arrays whose length it cannot see;
+    the binding refuses lists of any other length."""
+    with pytest.raises(ValueError, match="param_tensors has 2 entries for 3 tensors"):
+        binding.DefContext(30, 2, 2, 0.1, param_tensors=[4096, 8192], tensor_offsets=[0, 10, 20, 30])
+    with pytest.raises(ValueError, match="at least two entries"):
+        binding.DefContext(30, 2, 2, 0.1, params=4096, tensor_offsets=[0])
+    with pytest.raises(ValueError, match="params .* or param_tensors"):
+        binding.DefContext(30, 2, 2, 0.1)
+    ctx = binding.DefContext.__new__(binding.DefContext)      # no library context behind it
+    ctx.W, ctx.n_tensors, ctx._h = 2, 3, ctypes.c_void_p()
+    with pytest.raises(ValueError, match="5 gradient tensors given, W\\*n_tensors = 6"):
+        ctx._gtable([4096] * 5)
+    assert len(ctx._gtable([4096] * 6)) == 6
