@@ -23,12 +23,29 @@ constexpr uint32_t DEF_VEC_TILE = DEF_VEC_THREADS * DEF_VEC_QUADS * 4;   // indi
 // 16384 -> 79.6 %, 32768 -> 75 % of the HBM peak (the piece no longer fits in L2).
 constexpr uint32_t DEF_SUPER_TILES = 16384;
 // Dynamic LDS reserved per one-wave workgroup of the streaming kernel.  The kernel
-// does not touch it: with 160 KiB of LDS per compute unit the reservation caps
-// residency at 16 workgroups (4 waves per SIMD).  Fewer waves in flight keep the
-// window of addresses being read and written narrower, which the memory system
-// rewards: uncapped (32 per CU) 78-79 %, 20 per CU 80.4 %, 16 per CU 81 %,
-// 13 per CU 75 % of the HBM peak (same workload, random data).
-constexpr uint32_t DEF_VEC_LDS_RESERVE = 10240;
+// does not touch it: a compute unit has 160 KiB of LDS, handed out in 1280-byte
+// granules, so a reservation of 10240 bytes caps residency at 16 one-wave
+// workgroups (4 waves per SIMD) instead of the 32 that would otherwise fit.  What
+// the memory system rewards is a certain amount of traffic in flight per compute
+// unit, about 80 KiB of loads plus stores: fewer waves leave latency uncovered, more
+// widen the window of addresses being read and written and lose DRAM locality.  A
+// wave moves 1 KiB per stream, so the best residency depends on how many streams the
+// instantiation has (measured, d = 25.6 M, W = 16, random data, % of the HBM peak):
+//   g m e -> m e     (5 streams)  32: 78.8  18: 79.4  16: 80.2-81  14: 79.3  12: 73.6
+//   g m e -> m e w   (6 streams)  32: 75    16: 78.5  14: 79.2     12: 78.6  11: 76.8
+//   g e -> e         (3 streams)  32: 82.4  25: 82.8  21: 82.0     18: 74.2  16: 71.2
+//   g e -> e w       (4 streams)  32: 76    21: 78.3  18: 78.9     16: 78.3  14: 75.4
+constexpr uint32_t def_stream_lds_reserve(bool has_mu, bool has_dt)
+{
+    return has_mu ? (has_dt ? 11520u : 10240u)    // 14 / 16 workgroups per compute unit
+                  : (has_dt ? 8960u : 0u);        // 18 / as many as fit (32)
+}
+// The DEF output kernel (one wave per workgroup, every thread walks the W workers of its
+// four columns with four loads in flight): 8 workgroups per compute unit.  Measured at
+// the same shape: 256-thread workgroups, uncapped 75 %; one wave, uncapped 78 %, 16 per
+// compute unit 81 %, 12: 82.5 %, 8: 85.4 % of the HBM peak.
+constexpr uint32_t DEF_OUT_THREADS = 64;
+constexpr uint32_t DEF_OUT_LDS_RESERVE = 20480;
 // Steps that move more than this many bytes use non-temporal accesses for g, m, e.
 constexpr uint64_t DEF_NT_MIN_BYTES = 1ull << 30;
 

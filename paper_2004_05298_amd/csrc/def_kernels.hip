@@ -383,12 +383,12 @@ __device__ __forceinline__ void store_group(float *dst, uint64_t i, uint64_t d, 
 // DEF output y = x - (1/W) sum_k e_k (Algorithm 1 "Output").  One thread owns
 // four consecutive columns and walks the workers in order.
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(DEF_THREADS) void def_output_kernel(DefStepArgs a, float *y)
+__global__ __launch_bounds__(DEF_OUT_THREADS) void def_output_kernel(DefStepArgs a, float *y)
 {
-    const uint64_t i = ((uint64_t)blockIdx.x * DEF_THREADS + threadIdx.x) * 4;
+    const uint64_t i = ((uint64_t)blockIdx.x * DEF_OUT_THREADS + threadIdx.x) * 4;
     if (i >= a.d) return;
     v4f acc = (v4f)(0.0f);
-#pragma unroll 8
+#pragma unroll 4
     for (uint32_t k = 0; k < a.W; ++k) acc = acc + load4<true>(a.e + (uint64_t)k * a.ld + i);
     const v4f mean = acc / (float)a.W;
     store_group(y, i, a.d, load_x_group(a, i) - mean);
@@ -396,8 +396,8 @@ __global__ __launch_bounds__(DEF_THREADS) void def_output_kernel(DefStepArgs a, 
 
 // ---------------------------------------------------------------------------
 // Detached evaluation points for the current state, w_k = x - lambda*e_k
-// (Algorithm 1, "detach" line).  Same launch shape as the streaming pass: one wave
-// per (worker, 256 indices), blocked order so that x is served by L2 to all workers.
+// (Algorithm 1, "detach" line).  Work items as in the streaming pass: one wave per
+// (worker, 256 indices), blocked order so that x is served by L2 to all workers.
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(DEF_VEC_THREADS) void def_detach_kernel(DefStepArgs a, uint64_t tiles,
                                                                      uint64_t total)
@@ -450,7 +450,7 @@ __global__ __launch_bounds__(DEF_THREADS) void def_diag_partial_kernel(DefStepAr
     double s1 = 0.0, s2 = 0.0;
     if (i < a.d) {
         double acc[4] = {0.0, 0.0, 0.0, 0.0};
-#pragma unroll 4
+#pragma unroll 16
         for (uint32_t k = 0; k < a.W; ++k) {
             const v4f ev = load4<true>(a.e + (uint64_t)k * a.ld + i);   // padding columns hold zeros
 #pragma unroll
@@ -560,7 +560,7 @@ void def_describe_stream_kernel(const DefStepArgs &a, char *out, size_t cap)
     std::snprintf(out, cap,
                   "def_stream_vec4_kernel<mu=%d,wd=%d,detach=%d,tables=%d,threads=%u,quads=%u,nt=%d,order=%s,lds=%u>",
                   mu, wd, dt, tables, DEF_VEC_THREADS, DEF_VEC_QUADS, (int)streams_non_temporal(a), order,
-                  DEF_VEC_LDS_RESERVE);
+                  def_stream_lds_reserve(mu, dt));
 }
 
 // Picks the instantiation for (momentum, weight decay, detached points).  Whenever x
@@ -591,7 +591,8 @@ static void launch_vec4(const DefStepArgs &a, uint64_t tiles, uint64_t total, di
     constexpr uint32_t SUPER = DEF_SUPER_TILES;
     const bool mu = a.mu != 0.0f, wd = a.wd != 0.0f, dt = a.w != nullptr;
 #define DEF_LAUNCH_VEC(MU, WD, DT, MAP, SUP) \
-    def_stream_vec4_kernel<MU, WD, DT, TABLES, T, U, NT, NT, MAP><<<grid, block, DEF_VEC_LDS_RESERVE, st>>>(a, tiles, total, SUP)
+    def_stream_vec4_kernel<MU, WD, DT, TABLES, T, U, NT, NT, MAP>                                   \
+        <<<grid, block, def_stream_lds_reserve(MU, DT), st>>>(a, tiles, total, SUP)
     DEF_DISPATCH(DEF_LAUNCH_VEC);
 #undef DEF_LAUNCH_VEC
 }
@@ -665,15 +666,17 @@ hipError_t def_launch_detach(const DefStepArgs &a, hipStream_t st)
     const uint64_t tiles = (a.d + DEF_VEC_TILE - 1) / DEF_VEC_TILE;
     const uint64_t total = tiles * a.W;
     if (total > 0x7fffffffull - 8) return hipErrorInvalidConfiguration;
-    def_detach_kernel<<<dim3(grid_for(total)), dim3(DEF_VEC_THREADS), DEF_VEC_LDS_RESERVE, st>>>(a, tiles, total);
+    // two loads and one store of 1 KiB per wave: as many waves as fit (32 per compute unit:
+    // 79 % of the HBM peak; capped at 16: 62 %)
+    def_detach_kernel<<<dim3(grid_for(total)), dim3(DEF_VEC_THREADS), 0, st>>>(a, tiles, total);
     return hipGetLastError();
 }
 
 hipError_t def_launch_output(const DefStepArgs &a, float *y, hipStream_t st)
 {
     const uint64_t quads = (a.d + 3) / 4;
-    const uint64_t blocks = (quads + DEF_THREADS - 1) / DEF_THREADS;
+    const uint64_t blocks = (quads + DEF_OUT_THREADS - 1) / DEF_OUT_THREADS;
     if (blocks > 0x7fffffffull) return hipErrorInvalidConfiguration;
-    def_output_kernel<<<dim3((uint32_t)blocks), dim3(DEF_THREADS), 0, st>>>(a, y);
+    def_output_kernel<<<dim3((uint32_t)blocks), dim3(DEF_OUT_THREADS), DEF_OUT_LDS_RESERVE, st>>>(a, y);
     return hipGetLastError();
 }
