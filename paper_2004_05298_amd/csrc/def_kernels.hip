@@ -560,7 +560,7 @@ void def_describe_stream_kernel(const DefStepArgs &a, char *out, size_t cap)
     std::snprintf(out, cap,
                   "def_stream_vec4_kernel<mu=%d,wd=%d,detach=%d,tables=%d,threads=%u,quads=%u,nt=%d,order=%s,lds=%u>",
                   mu, wd, dt, tables, DEF_VEC_THREADS, DEF_VEC_QUADS, (int)streams_non_temporal(a), order,
-                  def_stream_lds_reserve(mu, dt));
+                  def_stream_lds_reserve(mu, dt, streams_non_temporal(a)));
 }
 
 // Picks the instantiation for (momentum, weight decay, detached points).  Whenever x
@@ -592,7 +592,7 @@ static void launch_vec4(const DefStepArgs &a, uint64_t tiles, uint64_t total, di
     const bool mu = a.mu != 0.0f, wd = a.wd != 0.0f, dt = a.w != nullptr;
 #define DEF_LAUNCH_VEC(MU, WD, DT, MAP, SUP) \
     def_stream_vec4_kernel<MU, WD, DT, TABLES, T, U, NT, NT, MAP>                                   \
-        <<<grid, block, def_stream_lds_reserve(MU, DT), st>>>(a, tiles, total, SUP)
+        <<<grid, block, def_stream_lds_reserve(MU, DT, NT), st>>>(a, tiles, total, SUP)
     DEF_DISPATCH(DEF_LAUNCH_VEC);
 #undef DEF_LAUNCH_VEC
 }
