@@ -128,6 +128,10 @@ def main() -> int:
     ap.add_argument("--detach", type=float, default=None, metavar="LAMBDA",
                     help="also write the detached evaluation points w_k = x - LAMBDA*e_k in the "
                          "same pass (24 instead of 20 bytes per worker and index)")
+    ap.add_argument("--with-y", action="store_true",
+                    help="def_step also writes DEF's output y = x - mean_k e_k every step (a second "
+                         "pass over the error memories; the paper needs y only when the model is "
+                         "evaluated, so the default step does not)")
     ap.add_argument("--graph", type=int, default=0, metavar="N",
                     help="capture N consecutive steps (device-side block draw) into one HIP graph "
                          "and time replays of it instead of eager launches; for the small, "
@@ -174,6 +178,9 @@ def main() -> int:
 
     w = wl.by_name(args.workload)
     variant = args.variant or ("def_a" if w.variant == "def_a" else "def")
+    if args.with_y and variant == "def_a":
+        print("bench.py: --with-y asks for DEF's output; DEF-A's output is x itself", file=sys.stderr)
+        return 2
     ld = wl.padded_ld(w.d)
     x = torch.from_numpy(wl.initial_params(w)).cuda()
     pool = wl.device_gradient_pool(w, ld)
@@ -222,16 +229,18 @@ def main() -> int:
         w_out = torch.empty((w.W, ld), dtype=torch.float32, device="cuda")
         ctx.set_detach(w_out, ld, args.detach)
 
+    y_out = torch.empty(w.d, dtype=torch.float32, device="cuda") if args.with_y else None
+
     def one_step(t):
         forced = w.forced_start(t)
         if forced is not None:
             ctx.force_next_start(forced)
         if grad_tables is not None:
-            ctx.step_tensors(grad_tables[t % w.pool], None)
+            ctx.step_tensors(grad_tables[t % w.pool], y_out)
         elif variant == "def_a":
             ctx.a_step(pool[t % w.pool], ld)
         else:
-            ctx.step(pool[t % w.pool], ld, None)
+            ctx.step(pool[t % w.pool], ld, y_out)
 
     t = 0
     for _ in range(args.warmup):
@@ -291,7 +300,7 @@ def main() -> int:
         }
     ctx.destroy()
 
-    ab = algorithmic_bytes(w, detach=args.detach is not None)
+    ab = algorithmic_bytes(w, y_out=args.with_y, detach=args.detach is not None)
     per_step = elapsed / args.steps
     value = ab["step"] / per_step / 1e9
     if kernel_ms:
@@ -310,7 +319,7 @@ def main() -> int:
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": w.name, "d": w.d, "W": w.W, "R": w.R, "B": w.B,
                    "n_tensors": w.n_tensors, "momentum": w.momentum,
-                   "weight_decay": w.weight_decay, "lr": w.lr, "variant": variant, "detach_lambda": args.detach,
+                   "weight_decay": w.weight_decay, "lr": w.lr, "variant": variant, "y_every_step": bool(args.with_y), "detach_lambda": args.detach,
                    "gradient_sets": w.pool, "inputs": "per-tensor pointers" if args.tensors else "flat", "launch": f"hip graph of {args.graph} steps" if args.graph else "eager",
                    "algorithmic_bytes_per_step": ab["step"]},
         "roofline": {"bound": "hbm", "kernel": kernel_name,
