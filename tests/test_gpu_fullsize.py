@@ -107,6 +107,48 @@ def test_whole_buffers_against_c_oracle(dev, name):
         ctx.destroy()
 
 
+@pytest.mark.timeout(600)
+def test_thousand_steps_stay_bit_identical(dev):
+    """A long run at the ResNet-56-shaped size: 1000 iterations cycling the gradient
+    pool, with a learning-rate drop, a seed change, a forced wrap and a y output on the
+    way; the state is compared with the C oracle's at the end and at three checkpoints."""
+    w = wl.by_name("resnet56_shaped")
+    d, W, ld = w.d, w.W, wl.padded_ld(w.d)
+    x0 = wl.initial_params(w)
+    host_pool = wl.gradient_pool(w, ld=ld, threads=16)
+    dev_pool = [torch.from_numpy(g).to(dev) for g in host_pool]
+    x = torch.from_numpy(x0).to(dev)
+    y = torch.empty(d, dtype=torch.float32, device=dev)
+    ora = DefOracleC(x0, W, w.R, w.lr, w.momentum, w.weight_decay, w.seed)
+    ctx = _ctx(w, x)
+    try:
+        for t in range(1000):
+            if t == 400:
+                ctx.set_lr(0.01)
+                ora.set_lr(0.01)
+            if t == 600:
+                ctx.set_seed(77)
+                ora.set_seed(77)
+            start = None
+            if t % 97 == 5:
+                start = d - w.B // 3                      # block crosses the end
+                ctx.force_next_start(start)
+            ctx.step(dev_pool[t % w.pool], ld, y if t % 250 == 249 else None)
+            s = ora.step(host_pool[t % w.pool], start=start)
+            assert ctx.last_block() == (s, w.B)
+            if t % 250 == 249:
+                torch.cuda.synchronize()
+                e, m, _ = ctx.state_tensors()
+                assert bit_equal(x.cpu().numpy(), ora.x), t
+                assert bit_equal(e.cpu().numpy()[:, :d], ora.e), t
+                assert bit_equal(m.cpu().numpy()[:, :d], ora.m), t
+                assert bit_equal(y.cpu().numpy(), ora.y()), t
+        print("[fullsize] resnet56_shaped: 1000 steps bit-identical (x, e, m, y at t = 250, 500, 750, 1000)",
+              flush=True)
+    finally:
+        ctx.destroy()
+
+
 def _sample_columns(w, starts, n_random):
     d, B = w.d, w.B
     rng = np.random.default_rng([w.seed, 99])
