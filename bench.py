@@ -36,7 +36,7 @@ HBM_PEAK_GBS = 8000.0   # MI355X HBM3E peak, GB/s
 # counters are taken again.
 MEASURED_TRAFFIC = {
     ("resnet50_shaped",
-     "def_stream_vec4_kernel<mu=1,wd=1,detach=0,tables=0,threads=64,quads=1,nt=1,order=blocked:16384,lds=10240>"): 8306273930,
+     "def_stream_vec4_kernel<mu=1,wd=1,detach=0,tables=0,threads=64,quads=1,nt=1,order=blocked:16384,lds=10240>"): 8306293271,
 }
 
 
@@ -128,6 +128,13 @@ def main() -> int:
     ap.add_argument("--detach", type=float, default=None, metavar="LAMBDA",
                     help="also write the detached evaluation points w_k = x - LAMBDA*e_k in the "
                          "same pass (24 instead of 20 bytes per worker and index)")
+    ap.add_argument("--workers", type=int, default=None, metavar="W",
+                    help="override the workload's number of workers on this GPU (W = 1 is one GPU's "
+                         "share when the workers are spread one per GPU)")
+    ap.add_argument("--split", action="store_true",
+                    help="run every iteration as def_pack + def_apply (the two halves between which "
+                         "a multi-GPU deployment would all-reduce the kept block), applying the "
+                         "local sum with divisor W")
     ap.add_argument("--with-y", action="store_true",
                     help="def_step also writes DEF's output y = x - mean_k e_k every step (a second "
                          "pass over the error memories; the paper needs y only when the model is "
@@ -177,6 +184,9 @@ def main() -> int:
         del src, dst
 
     w = wl.by_name(args.workload)
+    if args.workers is not None:
+        import dataclasses
+        w = dataclasses.replace(w, W=args.workers)
     variant = args.variant or ("def_a" if w.variant == "def_a" else "def")
     if args.with_y and variant == "def_a":
         print("bench.py: --with-y asks for DEF's output; DEF-A's output is x itself", file=sys.stderr)
@@ -235,7 +245,11 @@ def main() -> int:
         forced = w.forced_start(t)
         if forced is not None:
             ctx.force_next_start(forced)
-        if grad_tables is not None:
+        if args.split:
+            block = (ctx.pack_tensors(grad_tables[t % w.pool]) if grad_tables is not None
+                     else ctx.pack(pool[t % w.pool], ld))
+            ctx.apply(block, float(w.W), y_out)
+        elif grad_tables is not None:
             ctx.step_tensors(grad_tables[t % w.pool], y_out)
         elif variant == "def_a":
             ctx.a_step(pool[t % w.pool], ld)
@@ -319,7 +333,7 @@ def main() -> int:
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": w.name, "d": w.d, "W": w.W, "R": w.R, "B": w.B,
                    "n_tensors": w.n_tensors, "momentum": w.momentum,
-                   "weight_decay": w.weight_decay, "lr": w.lr, "variant": variant, "y_every_step": bool(args.with_y), "detach_lambda": args.detach,
+                   "weight_decay": w.weight_decay, "lr": w.lr, "variant": variant, "split": bool(args.split), "y_every_step": bool(args.with_y), "detach_lambda": args.detach,
                    "gradient_sets": w.pool, "inputs": "per-tensor pointers" if args.tensors else "flat", "launch": f"hip graph of {args.graph} steps" if args.graph else "eager",
                    "algorithmic_bytes_per_step": ab["step"]},
         "roofline": {"bound": "hbm", "kernel": kernel_name,

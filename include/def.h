@@ -127,6 +127,41 @@ int def_step_tensors(def_ctx *ctx, const float *const *grad_ptrs, float *y_out);
 int def_a_step_tensors(def_ctx *ctx, const float *const *grad_ptrs);
 
 /*
+ * One iteration in two halves, for deployments in which the workers are spread over
+ * several GPUs (Sec. 5 "Settings": one worker per GPU, ring all-reduce): each GPU
+ * holds W >= 1 of the workers and a replica of x, and the compressed blocks are
+ * added across GPUs between the halves by a collective that the CALLER runs
+ * (C is linear, Assumption 3.3, so the sum of blocks is the block of the sum).
+ *
+ *   def_pack   Algorithm 1 up to the all-reduce line for this GPU's W workers:
+ *              momentum, error feedback, residual write-back (and the off-block
+ *              detached points if set), then the sum over the local workers of
+ *              their kept blocks,  block_sum[j] = sum_k C(p_k)[(s_t + j) mod d],
+ *              k ascending from +0, NOT divided.  *block_sum (if block_sum is
+ *              not NULL) receives the DEVICE address of that B-float vector,
+ *              owned by the library (the same buffer def_state_ptrs calls
+ *              avg_block); the caller may reduce it in place.  x is not touched.
+ *              Every GPU must use the same seed, step counter, d and R, so that
+ *              all draw the same block.  t <- t+1.
+ *   def_apply  the update line: x[(s_t + j) mod d] -= block[j] / divisor for
+ *              j < B, where block (DEVICE, B floats, may be *block_sum itself)
+ *              is the caller's reduced vector and divisor the total number of
+ *              workers over all GPUs; the in-block detached points (if set) and
+ *              the averaged block seen through def_state_ptrs are written too.
+ *              y_out as in def_step (with W local workers it subtracts the mean
+ *              of the LOCAL error memories; DEF's y over all GPUs needs one more
+ *              reduction of d floats by the caller, once, after training).
+ *
+ * def_pack followed by def_apply(*block_sum, W, y) on one GPU is bit-identical
+ * to def_step.  A def_pack must be followed by def_apply before the next
+ * def_pack or def_step (DEF_EINVAL otherwise, nothing changed); def_apply
+ * without a preceding def_pack, or with divisor <= 0, is DEF_EINVAL.
+ */
+int def_pack(def_ctx *ctx, const float *grads, uint64_t ld, const float **block_sum);
+int def_pack_tensors(def_ctx *ctx, const float *const *grad_ptrs, const float **block_sum);
+int def_apply(def_ctx *ctx, const float *block, float divisor, float *y_out);
+
+/*
  * DEF's output without stepping: y_out[i] = x[i] - (1/W) sum_k e_k[i] for the
  * current state (Algorithm 1 "Output").  y_out: DEVICE, d floats.
  */

@@ -39,6 +39,9 @@ SIGNATURES = {
     "def_a_step": (ctypes.c_int, [_vp, _vp, _u64]),
     "def_step_tensors": (ctypes.c_int, [_vp, ctypes.POINTER(_vp), _vp]),
     "def_a_step_tensors": (ctypes.c_int, [_vp, ctypes.POINTER(_vp)]),
+    "def_pack": (ctypes.c_int, [_vp, _vp, _u64, ctypes.POINTER(_vp)]),
+    "def_pack_tensors": (ctypes.c_int, [_vp, ctypes.POINTER(_vp), ctypes.POINTER(_vp)]),
+    "def_apply": (ctypes.c_int, [_vp, _vp, _f32, _vp]),
     "def_output": (ctypes.c_int, [_vp, _vp]),
     "def_set_detach": (ctypes.c_int, [_vp, _vp, _u64, _f32]),
     "def_detach": (ctypes.c_int, [_vp, _vp, _u64, _f32]),
@@ -214,6 +217,27 @@ class DefContext:
         tbl = self._gtable(grad_tensors)
         _check(self._lib.def_a_step_tensors(self._h, ctypes.cast(tbl, ctypes.POINTER(_vp))),
                "def_a_step_tensors")
+
+    def pack(self, grads, ld: int) -> int:
+        """First half of a split iteration; returns the device address of the B-float sum
+        of the local workers' kept blocks (see block_view)."""
+        out = _vp()
+        _check(self._lib.def_pack(self._h, _ptr(grads), ld, ctypes.byref(out)), "def_pack")
+        return out.value or 0
+
+    def pack_tensors(self, grad_tensors: Sequence) -> int:
+        tbl = self._gtable(grad_tensors)
+        out = _vp()
+        _check(self._lib.def_pack_tensors(self._h, ctypes.cast(tbl, ctypes.POINTER(_vp)), ctypes.byref(out)),
+               "def_pack_tensors")
+        return out.value or 0
+
+    def block_view(self, ptr: int):
+        """torch view [B] of the vector def_pack returned (what a collective would reduce)."""
+        return device_view(ptr, (-(-self.d // self.R),))
+
+    def apply(self, block, divisor: float, y_out=None) -> None:
+        _check(self._lib.def_apply(self._h, _ptr(block), divisor, _ptr(y_out)), "def_apply")
 
     def output(self, y_out) -> None:
         _check(self._lib.def_output(self._h, _ptr(y_out)), "def_output")

@@ -98,6 +98,7 @@ struct def_ctx {
     uint64_t last_start = 0;
     bool has_last = false;
     int last_flat = 0;
+    bool pending_apply = false;   // def_pack has run, def_apply has not
     hipStream_t stream = nullptr;
     int device = 0;           // GPU that was current in def_init; owns the stream and all buffers
     // device state owned by the library
@@ -163,8 +164,8 @@ DefStepArgs base_args(const def_ctx *c, uint64_t s)
     return a;
 }
 
-// The sequence of one iteration: streaming pass, average + update, optional y.
-int run_step(def_ctx *c, DefStepArgs &a, float *y_out)
+// The part of an iteration that is local to the workers: block draw and streaming pass.
+int run_stream(def_ctx *c, DefStepArgs &a)
 {
     if (c->device_draw) {
         // the kernels take the start the draw kernel leaves in device memory; a.s, drawn
@@ -180,8 +181,6 @@ int run_step(def_ctx *c, DefStepArgs &a, float *y_out)
         DEF_HIP(hipEventRecord(c->ev[2 * c->prof_n + 1], c->stream));
         ++c->prof_n;
     }
-    DEF_HIP(def_launch_average_update(a, c->stream));
-    if (y_out) DEF_HIP(def_launch_output(a, y_out, c->stream));
     c->last_start = a.s;
     c->has_last = true;
     // 1: flat addressing; 0: gradients and/or the parameters the pass reads come through tables
@@ -192,9 +191,71 @@ int run_step(def_ctx *c, DefStepArgs &a, float *y_out)
     return DEF_OK;
 }
 
+// The sequence of one iteration: streaming pass, average + update, optional y.
+int run_step(def_ctx *c, DefStepArgs &a, float *y_out)
+{
+    const int rc = run_stream(c, a);
+    if (rc != DEF_OK) return rc;
+    DEF_HIP(def_launch_average_update(a, c->stream));
+    if (y_out) DEF_HIP(def_launch_output(a, y_out, c->stream));
+    return DEF_OK;
+}
+
+// First half of a split iteration: streaming pass, then the sum of the local workers' blocks.
+int run_pack(def_ctx *c, DefStepArgs &a, const float **block_sum)
+{
+    const int rc = run_stream(c, a);
+    if (rc != DEF_OK) return rc;
+    DEF_HIP(def_launch_block_sum(a, c->stream));
+    c->pending_apply = true;
+    if (block_sum) *block_sum = c->avg;
+    return DEF_OK;
+}
+
 uint64_t next_start(const def_ctx *c)
 {
     return c->forced >= 0 ? (uint64_t)c->forced : draw_start(c->seed, c->t, c->d);
+}
+
+// The device copy of a table of W*L gradient pointers: one of the cached tables if the same
+// pointers were seen recently, else uploaded into a free or the least recently used slot.
+int device_grad_table(def_ctx *ctx, const float *const *grad_ptrs, const float ***out)
+{
+    const size_t n = (size_t)ctx->W * ctx->L;
+    for (size_t q = 0; q < n; ++q)
+        if (!grad_ptrs[q] || (uintptr_t)grad_ptrs[q] % 4 != 0) return DEF_EINVAL;
+    def_ctx::GradTable *use = nullptr, *free_slot = nullptr, *oldest = nullptr;
+    for (auto &tb : ctx->gtab) {
+        if (!tb.dev) {
+            if (!free_slot) free_slot = &tb;
+        } else if (tb.host.size() == n &&
+                   std::memcmp(tb.host.data(), grad_ptrs, n * sizeof(float *)) == 0) {
+            use = &tb;
+            break;
+        } else if (!oldest || tb.last_used < oldest->last_used) {
+            oldest = &tb;
+        }
+    }
+    if (!use) {
+        def_ctx::GradTable *slot = free_slot ? free_slot : oldest;
+        if (!slot->dev) {
+            DEF_HIP(hipMalloc((void **)&slot->dev, n * sizeof(float *)));
+        } else {
+            // a step in flight may still read the table that is being replaced
+            DEF_HIP(hipStreamSynchronize(ctx->stream));
+        }
+        slot->host.clear();                    // not a valid match until the copy has succeeded
+        DEF_HIP(hipMemcpy(slot->dev, grad_ptrs, n * sizeof(float *), hipMemcpyHostToDevice));
+        try {
+            slot->host.assign(grad_ptrs, grad_ptrs + n);
+        } catch (const std::bad_alloc &) {
+            return DEF_ENOMEM;
+        }
+        use = slot;
+    }
+    use->last_used = ++ctx->gtab_clock;
+    *out = use->dev;
+    return DEF_OK;
 }
 
 }  // namespace
@@ -321,7 +382,7 @@ int def_destroy(def_ctx *ctx)
 
 int def_step(def_ctx *ctx, const float *grads, uint64_t ld, float *y_out)
 {
-    if (!ctx || !grads || ld < ctx->d || (uintptr_t)grads % 4 != 0) return DEF_EINVAL;
+    if (!ctx || !grads || ld < ctx->d || (uintptr_t)grads % 4 != 0 || ctx->pending_apply) return DEF_EINVAL;
     if (y_out && (uintptr_t)y_out % 4 != 0) return DEF_EINVAL;
     DEF_ON_DEVICE(ctx);
     DefStepArgs a = base_args(ctx, next_start(ctx));
@@ -331,6 +392,45 @@ int def_step(def_ctx *ctx, const float *grads, uint64_t ld, float *y_out)
     return run_step(ctx, a, y_out);
 }
 
+int def_pack(def_ctx *ctx, const float *grads, uint64_t ld, const float **block_sum)
+{
+    if (!ctx || !grads || ld < ctx->d || (uintptr_t)grads % 4 != 0 || ctx->pending_apply) return DEF_EINVAL;
+    DEF_ON_DEVICE(ctx);
+    DefStepArgs a = base_args(ctx, next_start(ctx));
+    a.g_flat = grads;
+    a.ldg = ld;
+    a.g_ptrs = nullptr;
+    return run_pack(ctx, a, block_sum);
+}
+
+int def_pack_tensors(def_ctx *ctx, const float *const *grad_ptrs, const float **block_sum)
+{
+    if (!ctx || !grad_ptrs || ctx->pending_apply) return DEF_EINVAL;
+    DEF_ON_DEVICE(ctx);
+    const float **table = nullptr;
+    const int rc = device_grad_table(ctx, grad_ptrs, &table);
+    if (rc != DEF_OK) return rc;
+    DefStepArgs a = base_args(ctx, next_start(ctx));
+    a.g_flat = nullptr;
+    a.ldg = 0;
+    a.g_ptrs = table;
+    return run_pack(ctx, a, block_sum);
+}
+
+int def_apply(def_ctx *ctx, const float *block, float divisor, float *y_out)
+{
+    if (!ctx || !block || (uintptr_t)block % 4 != 0 || !(divisor > 0.0f) || !ctx->pending_apply)
+        return DEF_EINVAL;
+    if (y_out && (uintptr_t)y_out % 4 != 0) return DEF_EINVAL;
+    DEF_ON_DEVICE(ctx);
+    DefStepArgs a = base_args(ctx, ctx->last_start);
+    if (ctx->device_draw) a.ctl = ctx->ctl;      // the start the pack half drew on the device
+    DEF_HIP(def_launch_apply_block(a, block, divisor, ctx->stream));
+    ctx->pending_apply = false;
+    if (y_out) DEF_HIP(def_launch_output(a, y_out, ctx->stream));
+    return DEF_OK;
+}
+
 int def_a_step(def_ctx *ctx, const float *grads, uint64_t ld)
 {
     return def_step(ctx, grads, ld, nullptr);
@@ -338,46 +438,16 @@ int def_a_step(def_ctx *ctx, const float *grads, uint64_t ld)
 
 int def_step_tensors(def_ctx *ctx, const float *const *grad_ptrs, float *y_out)
 {
-    if (!ctx || !grad_ptrs) return DEF_EINVAL;
+    if (!ctx || !grad_ptrs || ctx->pending_apply) return DEF_EINVAL;
     if (y_out && (uintptr_t)y_out % 4 != 0) return DEF_EINVAL;
-    const size_t n = (size_t)ctx->W * ctx->L;
-    for (size_t q = 0; q < n; ++q)
-        if (!grad_ptrs[q] || (uintptr_t)grad_ptrs[q] % 4 != 0) return DEF_EINVAL;
     DEF_ON_DEVICE(ctx);
-    def_ctx::GradTable *use = nullptr, *free_slot = nullptr, *oldest = nullptr;
-    for (auto &tb : ctx->gtab) {
-        if (!tb.dev) {
-            if (!free_slot) free_slot = &tb;
-        } else if (tb.host.size() == n &&
-                   std::memcmp(tb.host.data(), grad_ptrs, n * sizeof(float *)) == 0) {
-            use = &tb;
-            break;
-        } else if (!oldest || tb.last_used < oldest->last_used) {
-            oldest = &tb;
-        }
-    }
-    if (!use) {
-        def_ctx::GradTable *slot = free_slot ? free_slot : oldest;
-        if (!slot->dev) {
-            DEF_HIP(hipMalloc((void **)&slot->dev, n * sizeof(float *)));
-        } else {
-            // a step in flight may still read the table that is being replaced
-            DEF_HIP(hipStreamSynchronize(ctx->stream));
-        }
-        slot->host.clear();                    // not a valid match until the copy has succeeded
-        DEF_HIP(hipMemcpy(slot->dev, grad_ptrs, n * sizeof(float *), hipMemcpyHostToDevice));
-        try {
-            slot->host.assign(grad_ptrs, grad_ptrs + n);
-        } catch (const std::bad_alloc &) {
-            return DEF_ENOMEM;
-        }
-        use = slot;
-    }
-    use->last_used = ++ctx->gtab_clock;
+    const float **table = nullptr;
+    const int rc = device_grad_table(ctx, grad_ptrs, &table);
+    if (rc != DEF_OK) return rc;
     DefStepArgs a = base_args(ctx, next_start(ctx));
     a.g_flat = nullptr;
     a.ldg = 0;
-    a.g_ptrs = use->dev;
+    a.g_ptrs = table;
     return run_step(ctx, a, y_out);
 }
 

@@ -35,7 +35,7 @@ constexpr uint32_t DEF_SUPER_TILES = 16384;
 //   g m e -> m e w   (6 streams)  32: 75    16: 78.5  14: 79.2     12: 78.6  11: 76.8
 //   g e -> e         (3 streams)  32: 82.4  25: 82.8  21: 82.0     18: 74.2  16: 71.2
 //   g e -> e w       (4 streams)  32: 76    21: 78.3  18: 78.9     16: 78.3  14: 75.4
-// Steps small enough to be served by the caches (see DEF_NT_MIN_BYTES) run uncapped: at
+// Steps whose state the caches can hold (see DEF_NT_MIN_STATE_BYTES) run uncapped: at
 // 137 MB per step 32 per compute unit is 2-3 % faster than 16.
 constexpr uint32_t def_stream_lds_reserve(bool has_mu, bool has_dt, bool non_temporal)
 {
@@ -49,8 +49,9 @@ constexpr uint32_t def_stream_lds_reserve(bool has_mu, bool has_dt, bool non_tem
 // compute unit 81 %, 12: 82.5 %, 8: 85.4 % of the HBM peak.
 constexpr uint32_t DEF_OUT_THREADS = 64;
 constexpr uint32_t DEF_OUT_LDS_RESERVE = 20480;
-// Steps that move more than this many bytes use non-temporal accesses for g, m, e.
-constexpr uint64_t DEF_NT_MIN_BYTES = 1ull << 30;
+// When the state a step reads again next time (m, e, and x if the pass reads it) is larger
+// than this, g, m and e are accessed non-temporally; below it they are cached normally.
+constexpr uint64_t DEF_NT_MIN_STATE_BYTES = 224ull << 20;
 
 // Device-resident copy of the draw state, used when the block start is drawn on the
 // device so that a captured HIP graph of a step can be replayed (each replay advances t).
@@ -108,6 +109,10 @@ hipError_t def_launch_ctl_set(DefCtl *ctl, uint32_t mask, uint64_t t, uint64_t s
 hipError_t def_launch_stream(const DefStepArgs &a, hipStream_t st);
 // Cross-worker average of the compact blocks (LDS-staged) and parameter update.
 hipError_t def_launch_average_update(const DefStepArgs &a, hipStream_t st);
+// The same in two halves: avg[j] = sum_k msg_k[j] (no division, x untouched), and
+// x[(s+j) mod d] -= block[j] / divisor (also avg[j] = block[j] / divisor, and w on the block).
+hipError_t def_launch_block_sum(const DefStepArgs &a, hipStream_t st);
+hipError_t def_launch_apply_block(const DefStepArgs &a, const float *block, float divisor, hipStream_t st);
 // y = x - mean_k e_k.
 hipError_t def_launch_output(const DefStepArgs &a, float *y, hipStream_t st);
 // Error-memory statistics: ||e_t||^2, (1/W) sum_k ||e_k||^2, lambda*(t) and the distance

@@ -313,13 +313,13 @@ __device__ __forceinline__ float *param_addr(const DefStepArgs &a, uint64_t i)
 // ---------------------------------------------------------------------------
 constexpr int AVG_ROWS = 16;
 
-__global__ __launch_bounds__(DEF_THREADS) void def_average_update_kernel(DefStepArgs a)
+// Sum over the workers of one block column, k = 0..W-1 in order from +0 (valid for
+// threads whose column j_tile + threadIdx.x is below B; others get the padding's zeros).
+__device__ __forceinline__ float block_column_sum(const DefStepArgs &a, float (*stage)[DEF_AVG_TILE])
 {
-    __shared__ float stage[AVG_ROWS][DEF_AVG_TILE];
     const uint64_t j_tile = (uint64_t)blockIdx.x * DEF_AVG_TILE;
     const uint32_t lane = threadIdx.x & 63u;
     const uint32_t wave = threadIdx.x >> 6;
-
     float acc = 0.0f;
     for (uint32_t k0 = 0; k0 < a.W; k0 += AVG_ROWS) {
         const uint32_t rows = min((uint32_t)AVG_ROWS, a.W - k0);
@@ -331,22 +331,51 @@ __global__ __launch_bounds__(DEF_THREADS) void def_average_update_kernel(DefStep
         for (uint32_t r = 0; r < rows; ++r) acc = acc + stage[r][threadIdx.x];
         __syncthreads();
     }
-    const uint64_t j = j_tile + threadIdx.x;
-    if (j < a.B) {
-        const float cbar = acc / (float)a.W;                  // (1/W) sum_k C(p_k)
-        a.avg[j] = cbar;
-        uint64_t i = block_start_of(a) + j;
-        if (i >= a.d) i -= a.d;
-        float *px = param_addr(a, i);
-        const float x_new = *px - cbar;                       // x_{t+1} = x_t - C(p_t)
-        *px = x_new;
-        if (a.w) {
-            // inside the block e_{k,t+1} = +0 for every worker: w_k = x_{t+1} - lambda*0
-            const float scaled = a.lam * 0.0f;
-            const float wv = x_new - scaled;
-            for (uint32_t k = 0; k < a.W; ++k) a.w[(uint64_t)k * a.ldw + i] = wv;
-        }
+    return acc;
+}
+
+// x_{t+1} = x_t - cbar at block position j (Algorithm 1, update line), and the detached
+// points there: inside the block e_{k,t+1} = +0 for every worker, so w_k = x_{t+1} - lambda*0.
+__device__ __forceinline__ void apply_block_entry(const DefStepArgs &a, uint64_t j, float cbar)
+{
+    a.avg[j] = cbar;
+    uint64_t i = block_start_of(a) + j;
+    if (i >= a.d) i -= a.d;
+    float *px = param_addr(a, i);
+    const float x_new = *px - cbar;
+    *px = x_new;
+    if (a.w) {
+        const float scaled = a.lam * 0.0f;
+        const float wv = x_new - scaled;
+        for (uint32_t k = 0; k < a.W; ++k) a.w[(uint64_t)k * a.ldw + i] = wv;
     }
+}
+
+__global__ __launch_bounds__(DEF_THREADS) void def_average_update_kernel(DefStepArgs a)
+{
+    __shared__ float stage[AVG_ROWS][DEF_AVG_TILE];
+    const float acc = block_column_sum(a, stage);
+    const uint64_t j = (uint64_t)blockIdx.x * DEF_AVG_TILE + threadIdx.x;
+    if (j < a.B) apply_block_entry(a, j, acc / (float)a.W);      // (1/W) sum_k C(p_k)
+}
+
+// The two halves of the kernel above, for workers spread over several GPUs: the sum
+// over this GPU's workers (what an all-reduce would add up across GPUs) ...
+__global__ __launch_bounds__(DEF_THREADS) void def_block_sum_kernel(DefStepArgs a)
+{
+    __shared__ float stage[AVG_ROWS][DEF_AVG_TILE];
+    const float acc = block_column_sum(a, stage);
+    const uint64_t j = (uint64_t)blockIdx.x * DEF_AVG_TILE + threadIdx.x;
+    if (j < a.B) a.avg[j] = acc;
+}
+
+// ... and the update with a block that the caller has reduced: cbar = block[j] / divisor.
+// block may be the context's own avg buffer (each thread reads its entry before writing it).
+__global__ __launch_bounds__(DEF_THREADS) void def_apply_block_kernel(DefStepArgs a, const float *block,
+                                                                      float divisor)
+{
+    const uint64_t j = (uint64_t)blockIdx.x * DEF_THREADS + threadIdx.x;
+    if (j < a.B) apply_block_entry(a, j, block[j] / divisor);
 }
 
 // x[i..i+3] for a group that may be cut by d (missing entries are 0): flat vector, or
@@ -539,14 +568,18 @@ uint32_t grid_for(uint64_t total)
 
 }  // namespace
 
-// The three streams are touched once per step.  When a step's working set is far
-// larger than the 256 MiB Infinity Cache, non-temporal accesses keep them from
-// churning L2 and that cache (+20 % at 8 GB per step); when it is of the cache's
-// order, ordinary cached accesses let the state stay resident from one step to the
-// next (+3 % at 137 MB, +8 % at 480 MB per step).
+// g, m and e are touched once per step.  What can stay in the 256 MiB Infinity Cache
+// from one step to the next is the state that the next step reads again: m, e and, if
+// the pass reads it, x.  While that fits, ordinary cached accesses win (m + e of 218 MB:
+// 83 % of the HBM peak against 77.5 % with non-temporal accesses); once it does not,
+// cached accesses only churn the caches and non-temporal ones win (246 MB: 74.6 against
+// 77.9 %; 306 MB: 72 against 83 %; 3.3 GB: +20 %).
 static bool streams_non_temporal(const DefStepArgs &a)
 {
-    return (uint64_t)a.W * a.d * 20ull > DEF_NT_MIN_BYTES;
+    const uint64_t rows = (uint64_t)a.W * a.ld * sizeof(float);
+    const bool reads_x = a.wd != 0.0f || a.w != nullptr;
+    const uint64_t resident = rows * (a.mu != 0.0f ? 2u : 1u) + (reads_x ? a.d * sizeof(float) : 0u);
+    return resident > DEF_NT_MIN_STATE_BYTES;
 }
 
 void def_describe_stream_kernel(const DefStepArgs &a, char *out, size_t cap)
@@ -626,6 +659,22 @@ hipError_t def_launch_average_update(const DefStepArgs &a, hipStream_t st)
     const uint64_t tiles = (a.B + DEF_AVG_TILE - 1) / DEF_AVG_TILE;
     if (tiles > 0x7fffffffull) return hipErrorInvalidConfiguration;
     def_average_update_kernel<<<dim3((uint32_t)tiles), dim3(DEF_THREADS), 0, st>>>(a);
+    return hipGetLastError();
+}
+
+hipError_t def_launch_block_sum(const DefStepArgs &a, hipStream_t st)
+{
+    const uint64_t tiles = (a.B + DEF_AVG_TILE - 1) / DEF_AVG_TILE;
+    if (tiles > 0x7fffffffull) return hipErrorInvalidConfiguration;
+    def_block_sum_kernel<<<dim3((uint32_t)tiles), dim3(DEF_THREADS), 0, st>>>(a);
+    return hipGetLastError();
+}
+
+hipError_t def_launch_apply_block(const DefStepArgs &a, const float *block, float divisor, hipStream_t st)
+{
+    const uint64_t blocks = (a.B + DEF_THREADS - 1) / DEF_THREADS;
+    if (blocks > 0x7fffffffull) return hipErrorInvalidConfiguration;
+    def_apply_block_kernel<<<dim3((uint32_t)blocks), dim3(DEF_THREADS), 0, st>>>(a, block, divisor);
     return hipGetLastError();
 }
 

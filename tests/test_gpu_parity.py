@@ -53,9 +53,11 @@ def fetch_avg(ctx):
 
 def run_case(dev, w, *, weight_decay=None, momentum=None, T=None, flat_params=True,
              mode="flat", misalign=0, ld=None, oracle="np", check_every_step=True,
-             with_y=True, special=None, variant=None, forced=None, detach=None, ldw=None):
+             with_y=True, special=None, variant=None, forced=None, detach=None, ldw=None,
+             split=False):
     """Run T steps on both sides and compare.  mode: "flat" (one gradient buffer
-    [W][ld]) or "tensors" (one allocation per worker and tensor)."""
+    [W][ld]) or "tensors" (one allocation per worker and tensor).  split: every
+    iteration is def_pack followed by def_apply of the returned sum with divisor W."""
     binding = _binding()
     wd = w.weight_decay if weight_decay is None else weight_decay
     mu = w.momentum if momentum is None else momentum
@@ -124,7 +126,14 @@ def run_case(dev, w, *, weight_decay=None, momentum=None, T=None, flat_params=Tr
             if start is not None:
                 ctx.force_next_start(start)
             want_y = with_y and variant != "def_a" and (t == T - 1 or t == T // 2)
-            if mode == "flat":
+            if split:
+                if mode == "flat":
+                    block = ctx.pack(gdev[t % w.pool][1], ld)
+                else:
+                    block = ctx.pack_tensors(gdev[t % w.pool])
+                assert block == ctx.state_ptrs()[2]
+                ctx.apply(block, float(W), y_dev if want_y else None)
+            elif mode == "flat":
                 view = gdev[t % w.pool][1]
                 if variant == "def_a":
                     ctx.a_step(view, ld)
@@ -483,3 +492,107 @@ def test_invalid_arguments_change_nothing(dev):
     torch.cuda.synchronize()
     assert ctx.get_step() == 1
     ctx.destroy()
+
+
+# --------------------------------------------------------------------------- #
+# The iteration in two halves (workers spread over several GPUs)
+# --------------------------------------------------------------------------- #
+@pytest.mark.parametrize("mode,flat_params,wd,mu,detach", [
+    ("flat", True, 1e-4, 0.9, None),
+    ("flat", True, 0.0, 0.0, LAM32),
+    ("flat", True, 1e-3, 0.9, LAM32),
+    ("tensors", False, 1e-4, 0.9, None),
+])
+def test_pack_then_apply_is_the_step(dev, mode, flat_params, wd, mu, detach):
+    """def_pack + def_apply(own sum, divisor W) must equal def_step, hence the oracle, bit for bit."""
+    w = wl.shrunk(wl.by_name("resnet56_shaped"), 30011, 9, T=8)
+    exact = run_case(dev, w, weight_decay=wd, momentum=mu, T=8, mode=mode, flat_params=flat_params,
+                     detach=detach, split=True)
+    assert all(exact.values()), exact
+
+
+@pytest.mark.parametrize("groups,per_group,wd", [(2, 1, 0.0), (2, 1, 1e-3), (2, 4, 0.0), (3, 2, 1e-3)])
+def test_worker_groups_with_a_summed_block_match_the_full_oracle(dev, groups, per_group, wd):
+    """The deployment of Sec. 5 on one device: `groups` contexts stand for GPUs, each with
+    `per_group` workers and its own replica of x; the blocks def_pack returns are added
+    (the stand-in for the all-reduce) and every context applies the sum with divisor
+    W = groups*per_group.  The oracle runs all W workers in one place.  With one worker per
+    group and two groups the sum a + b is the oracle's own ((+0 + a) + b): bit-identical;
+    otherwise the groups' partial sums associate differently and the 1e-6 tolerance applies."""
+    binding = _binding()
+    W = groups * per_group
+    base = wl.shrunk(wl.by_name("resnet56_shaped"), 20021, 7)
+    d, ld, R, T = base.d, wl.padded_ld(base.d), base.R, 10
+    rng = np.random.default_rng(1234)
+    x0 = wl.initial_params(base)
+    grads = [(rng.standard_normal((W, d)) * 1e-2).astype(np.float32) for _ in range(3)]
+    ora = DefOracle(x0, W, R, base.lr, 0.9, wd, base.seed)
+    stream = torch.cuda.current_stream().cuda_stream
+    xs = [torch.from_numpy(x0).to(dev) for _ in range(groups)]
+    ctxs = [binding.DefContext(d, per_group, R, base.lr, 0.9, wd, base.seed, params=xs[q], stream=stream)
+            for q in range(groups)]
+    gdev = []
+    for g in grads:
+        per = []
+        for q in range(groups):
+            buf = torch.zeros(per_group, ld, dtype=torch.float32, device=dev)
+            buf[:, :d].copy_(torch.from_numpy(g[q * per_group:(q + 1) * per_group]))
+            per.append(buf)
+        gdev.append(per)
+    try:
+        for t in range(T):
+            views = [ctxs[q].block_view(ctxs[q].pack(gdev[t % 3][q], ld)) for q in range(groups)]
+            total = views[0].clone()
+            for v in views[1:]:
+                total = total + v
+            for q in range(groups):
+                ctxs[q].apply(total, float(W))
+            s = ora.step(grads[t % 3])
+            assert all(c.last_block() == (s, base.B) for c in ctxs)
+        torch.cuda.synchronize()
+        exact = groups == 2 and per_group == 1
+        xg = [x.cpu().numpy() for x in xs]
+        for q in range(1, groups):
+            assert bit_equal(xg[q], xg[0])                 # replicas never diverge
+        e = np.concatenate([c.state_tensors()[0].cpu().numpy()[:, :d] for c in ctxs])
+        m = np.concatenate([c.state_tensors()[1].cpu().numpy()[:, :d] for c in ctxs])
+        avg = ctxs[0].state_tensors()[2].cpu().numpy()
+        assert_close("x", xg[0], ora.x)
+        assert_close("e", e, ora.e)
+        assert_close("m", m, ora.m)
+        assert_close("averaged block", avg, ora.compact_block())
+        mask = in_block_mask(d, ora.last_start, base.B)
+        assert (bits(e[:, mask]) == 0).all()
+        if exact or wd == 0.0:
+            assert bit_equal(e, ora.e) and bit_equal(m, ora.m)   # x never enters e or m without decay
+        if exact:
+            assert bit_equal(xg[0], ora.x) and bit_equal(avg, ora.compact_block())
+        print(f"[parity] {groups} groups x {per_group} workers wd={wd}: bit-identical x={bit_equal(xg[0], ora.x)} "
+              f"e={bit_equal(e, ora.e)} m={bit_equal(m, ora.m)}", flush=True)
+    finally:
+        for c in ctxs:
+            c.destroy()
+
+
+def test_split_iteration_call_order_is_enforced(dev):
+    binding = _binding()
+    d, W = 1000, 2
+    x = torch.zeros(d, device=dev)
+    g = torch.ones(W, 1024, device=dev)
+    ctx = binding.DefContext(d, W, 4, 0.1, 0.9, 0.0, 1, params=x, stream=torch.cuda.current_stream().cuda_stream)
+    try:
+        with pytest.raises(binding.DefError):
+            ctx.apply(x, 2.0)                              # nothing packed
+        block = ctx.pack(g, 1024)
+        for call in (lambda: ctx.step(g, 1024), lambda: ctx.pack(g, 1024), lambda: ctx.a_step(g, 1024),
+                     lambda: ctx.apply(block, 0.0), lambda: ctx.apply(None, 2.0)):
+            with pytest.raises(binding.DefError) as ei:
+                call()
+            assert ei.value.status == binding.DEF_EINVAL
+        assert ctx.get_step() == 1
+        ctx.apply(block, 2.0)
+        ctx.step(g, 1024)
+        torch.cuda.synchronize()
+        assert ctx.get_step() == 2
+    finally:
+        ctx.destroy()
