@@ -71,8 +71,10 @@ def test_device_draw_matches_host_draw_and_oracle(dev):
         ctx.destroy()
 
 
-@pytest.mark.parametrize("steps_per_graph", [1, 3])
-def test_graph_replays_follow_the_oracle(dev, steps_per_graph):
+@pytest.mark.parametrize("steps_per_graph,split", [(1, False), (3, False), (2, True)])
+def test_graph_replays_follow_the_oracle(dev, steps_per_graph, split):
+    """split: every captured iteration is def_pack + def_apply of the local sum (the two
+    halves a multi-GPU caller would put a collective between)."""
     stream = torch.cuda.Stream()
     w, ld, pool, gdev, x, ora, ctx = _setup(dev, stream)
     n = steps_per_graph
@@ -89,7 +91,10 @@ def test_graph_replays_follow_the_oracle(dev, steps_per_graph):
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph, stream=stream):
             for q in range(n):
-                ctx.step(static[q], ld, y if q == n - 1 else None)
+                if split:
+                    ctx.apply(ctx.pack(static[q], ld), float(w.W), y if q == n - 1 else None)
+                else:
+                    ctx.step(static[q], ld, y if q == n - 1 else None)
         stream.synchronize()
         _check_state(ctx, x, ora, w.d, "capture must not execute anything")
         t = 2
