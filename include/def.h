@@ -149,8 +149,10 @@ int def_a_step_tensors(def_ctx *ctx, const float *const *grad_ptrs);
  *              workers over all GPUs; the in-block detached points (if set) and
  *              the averaged block seen through def_state_ptrs are written too.
  *              y_out as in def_step (with W local workers it subtracts the mean
- *              of the LOCAL error memories; DEF's y over all GPUs needs one more
- *              reduction of d floats by the caller, once, after training).
+ *              of the LOCAL error memories; with the same W on every GPU, DEF's
+ *              y over all workers is the average of the GPUs' y_out, since all
+ *              hold the same x: one more reduction of d floats by the caller,
+ *              once, after training).
  *
  * def_pack followed by def_apply(*block_sum, W, y) on one GPU is bit-identical
  * to def_step.  A def_pack must be followed by def_apply before the next
