@@ -563,6 +563,15 @@ def test_worker_groups_with_a_summed_block_match_the_full_oracle(dev, groups, pe
         assert_close("averaged block", avg, ora.compact_block())
         mask = in_block_mask(d, ora.last_start, base.B)
         assert (bits(e[:, mask]) == 0).all()
+        # DEF's output over all workers = the average of the groups' outputs (same x, equal group sizes)
+        ys = []
+        for c in ctxs:
+            yq = torch.empty(d, dtype=torch.float32, device=dev)
+            c.output(yq)
+            ys.append(yq)
+        torch.cuda.synchronize()
+        y_all = (torch.stack(ys).double().mean(dim=0)).float().cpu().numpy()
+        assert_close("y", y_all, ora.y())
         if exact or wd == 0.0:
             assert bit_equal(e, ora.e) and bit_equal(m, ora.m)   # x never enters e or m without decay
         if exact:
