@@ -30,25 +30,34 @@ def build(force: bool = False) -> str:
     return _LIB
 
 
+def load(path: str):
+    """A CDLL of a build of def_oracle.c with the argument types set."""
+    L = ctypes.CDLL(path)
+    _declare(L)
+    return L
+
+
 def lib():
     global _lib
     if _lib is None:
-        L = ctypes.CDLL(build())
-        f32p = ctypes.POINTER(ctypes.c_float)
-        i64p = ctypes.POINTER(ctypes.c_int64)
-        L.def_oracle_step_f32.argtypes = [ctypes.c_int64, ctypes.c_int64, ctypes.c_int32,
-                                          ctypes.c_int64, ctypes.c_int64,
-                                          ctypes.c_float, ctypes.c_float, ctypes.c_float,
-                                          f32p, f32p, f32p, f32p, ctypes.c_int64, i64p, f32p]
-        L.def_oracle_step_f32.restype = None
-        L.def_oracle_y_f32.argtypes = [ctypes.c_int64, ctypes.c_int32, f32p, f32p, f32p]
-        L.def_oracle_y_f32.restype = None
-        L.def_oracle_detach_f32.argtypes = [ctypes.c_int64, ctypes.c_int32, ctypes.c_float, f32p, f32p, f32p]
-        L.def_oracle_detach_f32.restype = None
-        L.def_oracle_threads.restype = ctypes.c_int
-        L.def_oracle_set_threads.argtypes = [ctypes.c_int]
-        _lib = L
+        _lib = load(build())
     return _lib
+
+
+def _declare(L) -> None:
+    f32p = ctypes.POINTER(ctypes.c_float)
+    i64p = ctypes.POINTER(ctypes.c_int64)
+    L.def_oracle_step_f32.argtypes = [ctypes.c_int64, ctypes.c_int64, ctypes.c_int32,
+                                      ctypes.c_int64, ctypes.c_int64,
+                                      ctypes.c_float, ctypes.c_float, ctypes.c_float,
+                                      f32p, f32p, f32p, f32p, ctypes.c_int64, i64p, f32p]
+    L.def_oracle_step_f32.restype = None
+    L.def_oracle_y_f32.argtypes = [ctypes.c_int64, ctypes.c_int32, f32p, f32p, f32p]
+    L.def_oracle_y_f32.restype = None
+    L.def_oracle_detach_f32.argtypes = [ctypes.c_int64, ctypes.c_int32, ctypes.c_float, f32p, f32p, f32p]
+    L.def_oracle_detach_f32.restype = None
+    L.def_oracle_threads.restype = ctypes.c_int
+    L.def_oracle_set_threads.argtypes = [ctypes.c_int]
 
 
 def _p(a: np.ndarray):
@@ -58,7 +67,7 @@ def _p(a: np.ndarray):
 class DefOracleC:
     def __init__(self, x0, W: int, R: int, lr: float, momentum: float = 0.0,
                  weight_decay: float = 0.0, seed: int = 0, d: Optional[int] = None,
-                 index=None, threads: Optional[int] = None):
+                 index=None, threads: Optional[int] = None, library=None):
         self.dtype = np.dtype(np.float32)
         self.x = np.ascontiguousarray(x0, dtype=np.float32).copy()
         n = self.x.shape[0]
@@ -74,7 +83,7 @@ class DefOracleC:
         self.m = np.zeros((self.W, n), dtype=np.float32)
         self.last_start = None
         self.last_cbar_dense = np.zeros(n, dtype=np.float32)
-        self._lib = lib()
+        self._lib = library if library is not None else lib()   # (a mutated build, in the pin tests)
         if threads is not None:
             self._lib.def_oracle_set_threads(int(threads))
 

@@ -186,6 +186,25 @@ class DefOracle:
         return dict(bar_sq=bar_sq, mean_sq=mean_sq,
                     lam_star=(bar_sq / mean_sq if mean_sq > 0 else 0.0), dist=dist)
 
+    def diagnostics_workers(self) -> dict:
+        """Per-worker statistics of Sec. 3.2 item (1) / Appendix A, first display, in
+        float64: with e_t = (1/K) sum_k e_k, for every worker k
+          norm_sq[k]  = ||e_k||^2
+          inner[k]    = <e_t, e_k>
+          lam_star[k] = inner[k] / norm_sq[k]      (lambda*(k,t), the lambda that brings
+                        worker k's evaluation point x - lambda*e_k closest to y; 0 when
+                        e_k = 0)."""
+        e = self.e.astype(np.float64)
+        acc = np.zeros(e.shape[1], dtype=np.float64)
+        for k in range(self.W):
+            acc = acc + e[k]
+        mean_e = acc / np.float64(self.W)                           # e_t
+        norm_sq = np.array([np.sum(e[k] * e[k]) for k in range(self.W)], dtype=np.float64)
+        inner = np.array([np.sum(mean_e * e[k]) for k in range(self.W)], dtype=np.float64)
+        lam_star = np.array([inner[k] / norm_sq[k] if norm_sq[k] > 0 else 0.0
+                             for k in range(self.W)], dtype=np.float64)
+        return dict(norm_sq=norm_sq, inner=inner, lam_star=lam_star)
+
     def compact_block(self) -> np.ndarray:
         """The averaged block of the last step as the B-vector that would be
         all-reduced: entry j belongs to global index (s+j) mod d.  Needs the

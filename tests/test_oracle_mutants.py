@@ -39,14 +39,15 @@ def _pin_calls():
     calls.append(lambda: pins.test_detached_points_distance_identity())
     calls.append(lambda: pins.test_closed_loop_single_worker_follows_gradient_descent("np64", 1e-12))
     calls.append(lambda: _diag_pin(np.float64))
+    calls.append(lambda: _diag_pin(np.float64, pins.test_per_worker_statistics))
     return calls
 
 
-def _diag_pin(dtype):
+def _diag_pin(dtype, pin=None):
     saved = pins.DefOracle
     pins.DefOracle = pins.NUMPY_ORACLE
     try:
-        pins.test_diagnostics_against_norms_of_detached_points(dtype)
+        (pin or pins.test_diagnostics_against_norms_of_detached_points)(dtype)
     finally:
         pins.DefOracle = saved
 
@@ -116,6 +117,11 @@ MUTANTS = [
     ("diagnostics: mean_sq is a sum", "for k in range(self.W)) / self.W)\n        dist", "for k in range(self.W)))\n        dist"),
     ("diagnostics: lambda* inverted", "lam_star=(bar_sq / mean_sq if", "lam_star=(mean_sq / bar_sq if"),
     ("diagnostics: distance sign", "(e_bar - np.float64(lam) * e[k]) ** 2", "(e_bar + np.float64(lam) * e[k]) ** 2"),
+    ("per worker: inner product with worker 0", "np.sum(mean_e * e[k]) for k", "np.sum(mean_e * e[0]) for k"),
+    ("per worker: norm of worker 0", "np.sum(e[k] * e[k]) for k in range(self.W)], dtype", "np.sum(e[0] * e[0]) for k in range(self.W)], dtype"),
+    ("per worker: mean error not divided", "mean_e = acc / np.float64(self.W)", "mean_e = acc"),
+    ("per worker: lambda* inverted", "inner[k] / norm_sq[k] if norm_sq[k] > 0", "norm_sq[k] / inner[k] if norm_sq[k] > 0"),
+    ("per worker: inner product with itself", "np.sum(mean_e * e[k]) for k", "np.sum(e[k] * e[k]) for k"),
 ]
 
 PHILOX_MUTANTS = [
@@ -145,3 +151,61 @@ def test_planted_generator_mistake_is_caught(name, old, new):
     assert _PHILOX_SRC.count(old) == 1, f"mutation target not unique/present: {old!r}"
     mod, ph = _load(_SRC, _PHILOX_SRC.replace(old, new))
     assert _run_pins(mod, ph) >= 1, f"no pin noticed: {name}"
+
+
+# --------------------------------------------------------------------------- #
+# The plain C oracle: planted mistakes in a private build of def_oracle.c must
+# break its bit-agreement with the (mutant-pinned) numpy oracle.
+# --------------------------------------------------------------------------- #
+_C_SRC_PATH = os.path.join(os.path.dirname(real_module.__file__), "def_oracle.c")
+_C_SRC = open(_C_SRC_PATH).read()
+
+C_MUTANTS = [
+    ("detach reads worker 0's error", "float scaled = lambda * e[(size_t)k * (size_t)n + (size_t)c];",
+     "float scaled = lambda * e[(size_t)c];"),
+    ("detach writes worker 0's row", "w[(size_t)k * (size_t)n + (size_t)c] = x[c] - scaled;",
+     "w[(size_t)c] = x[c] - scaled;"),
+    ("detach sign", "w[(size_t)k * (size_t)n + (size_t)c] = x[c] - scaled;",
+     "w[(size_t)k * (size_t)n + (size_t)c] = x[c] + scaled;"),
+    ("detach ignores lambda", "float scaled = lambda * e[(size_t)k * (size_t)n + (size_t)c];",
+     "float scaled = e[(size_t)k * (size_t)n + (size_t)c];"),
+    ("momentum dropped", "mk = carried + gk; ", "mk = gk;           "),
+    ("block not zeroed", "ek[c] = 0.0f;                       /* ... and the residual there is +0  */",
+     "ek[c] = p;"),
+    ("no wrap", "if (j < 0) j += d;", ""),
+    ("y not averaged", "y[c] = x[c] - acc / (float)W;", "y[c] = x[c] - acc;"),
+    ("sum instead of mean", "cbar[c] = cbar[c] / (float)W;", ""),
+]
+
+
+def _c_agreement(library):
+    saved = pins.DefOracleC
+    if library is not None:
+        pins.DefOracleC = lambda *a, **kw: saved(*a, library=library, **kw)
+    try:
+        pins.test_numpy_and_c_oracles_agree_bitwise()
+    finally:
+        pins.DefOracleC = saved
+
+
+def _build_c(src, tmp_path, tag):
+    import subprocess
+    from oracle import c_oracle
+    c_file = tmp_path / f"oracle_{tag}.c"
+    so_file = tmp_path / f"liboracle_{tag}.so"
+    c_file.write_text(src)
+    subprocess.check_call(["gcc", "-O2", "-ffp-contract=off", "-fopenmp", "-shared", "-fPIC",
+                           "-o", str(so_file), str(c_file)])
+    return c_oracle.load(str(so_file))
+
+
+def test_unmodified_c_build_agrees(tmp_path):
+    _c_agreement(_build_c(_C_SRC, tmp_path, "clean"))
+
+
+@pytest.mark.parametrize("name,old,new", C_MUTANTS, ids=[m[0] for m in C_MUTANTS])
+def test_planted_c_mistake_is_caught(tmp_path, name, old, new):
+    assert _C_SRC.count(old) == 1, f"mutation target not unique/present: {old!r}"
+    library = _build_c(_C_SRC.replace(old, new), tmp_path, "mutant")
+    with pytest.raises(AssertionError):
+        _c_agreement(library)

@@ -391,6 +391,50 @@ def test_diagnostics_against_norms_of_detached_points(dtype):
     assert fresh == dict(bar_sq=0.0, mean_sq=0.0, lam_star=0.0, dist=0.0)
 
 
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+def test_per_worker_statistics(dtype):
+    """Sec. 3.2 item (1) / Appendix A, first display: lambda*(k,t) = <e_t, e_k>/||e_k||^2
+    is the lambda at which worker k's own evaluation point x - lambda*e_k is closest to
+    y.  Checked without the formula: worker k's squared distance to y, measured with
+    numpy's norm at three lambdas, is a parabola whose vertex must be lambda*(k,t) and
+    whose curvature must be ||e_k||^2; the workers' inner products average to
+    ||e_t||^2 = ||x - y||^2; one worker alone gives lambda* = 1."""
+    d, W, R, T = 70, 4, 6, 12
+    rng = np.random.default_rng(95)
+    o = DefOracle(rng.standard_normal(d), W, R, 0.1, 0.9, 0.0, 5, dtype=dtype)
+    for t in range(T):
+        o.step(rng.standard_normal((W, d)))
+    e64 = o.e.astype(np.float64)
+    x64 = o.x.astype(np.float64)
+    y64 = x64 - e64.mean(axis=0)
+    pw = o.diagnostics_workers()
+    assert pw["norm_sq"].shape == pw["inner"].shape == pw["lam_star"].shape == (W,)
+
+    def dist_k(k, lam):
+        return float(np.linalg.norm((x64 - lam * e64[k]) - y64) ** 2)
+
+    for k in range(W):
+        d0, d1, d2 = dist_k(k, 0.0), dist_k(k, 1.0), dist_k(k, 2.0)
+        a2 = (d2 - 2 * d1 + d0) / 2.0
+        a1 = d1 - d0 - a2
+        vertex = -a1 / (2 * a2)
+        assert pw["lam_star"][k] == pytest.approx(vertex, rel=1e-9), k
+        assert pw["norm_sq"][k] == pytest.approx(a2, rel=1e-9), k
+        assert pw["norm_sq"][k] == pytest.approx(np.linalg.norm(e64[k]) ** 2, rel=1e-11), k
+        assert pw["inner"][k] == pytest.approx(-a1 / 2.0, rel=1e-9), k
+        best = dist_k(k, pw["lam_star"][k])
+        assert best <= min(dist_k(k, pw["lam_star"][k] - 1e-3), dist_k(k, pw["lam_star"][k] + 1e-3))
+    assert len(set(np.round(pw["lam_star"], 12))) == W          # the workers differ
+    assert np.mean(pw["inner"]) == pytest.approx(np.linalg.norm(x64 - y64) ** 2, rel=1e-11)
+    one = DefOracle(rng.standard_normal(d), 1, R, 0.1, 0.9, 0.0, 5, dtype=dtype)
+    for t in range(5):
+        one.step(rng.standard_normal((1, d)))
+    p1 = one.diagnostics_workers()
+    assert p1["lam_star"][0] == pytest.approx(1.0, rel=1e-12) and p1["inner"][0] == p1["norm_sq"][0] > 0
+    fresh = DefOracle(np.zeros(d), 2, R, 0.1, dtype=dtype).diagnostics_workers()
+    assert not fresh["norm_sq"].any() and not fresh["inner"].any() and not fresh["lam_star"].any()
+
+
 def test_error_memory_stationary_moments_and_bounds():
     """Gradients g_k = c + noise_k that do not depend on x (mu = 0): an index that
     was last kept `a` steps ago holds e_k = eta*(a*c + sum of a noise terms).  With
@@ -595,6 +639,12 @@ def test_numpy_and_c_oracles_agree_bitwise():
         assert np.array_equal(bits(np.asarray(getattr(a, n))), bits(np.asarray(getattr(b, n))))
     assert np.array_equal(bits(a.y()), bits(b.y()))
     assert np.array_equal(bits(a.compact_block()), bits(b.compact_block()))
+    # detached points, lambda neither 0 nor 1 and W > 1, so that every row and the scale matter
+    # (the numpy side is pinned by the special cases, the distance identity and its mutants)
+    wa, wb = a.detached_points(0.3), b.detached_points(0.3)
+    assert wa.shape == wb.shape == (W, d)
+    assert np.array_equal(bits(wa), bits(wb))
+    assert len({wa[k].tobytes() for k in range(W)}) == W
 
 
 def test_tiny_workload_digest_unchanged():
