@@ -27,6 +27,13 @@
  *     drives several GPUs need not switch devices around calls into a context.
  *   - Every function returns DEF_OK (0) or a negative def_status.  No function
  *     throws or aborts.  A call that returns DEF_EINVAL has changed nothing.
+ *     A step that returns DEF_EHIP because its streaming launch (or anything before
+ *     it) failed has not advanced the step counter, has consumed no forced start and
+ *     has changed no state buffer; with the device draw on, the device's copy of the
+ *     counter is put back to the host's on the same stream.  If a later launch of the
+ *     same step fails (the separate averaging kernel, the y output) the streaming
+ *     pass has already been enqueued: the context is then mid-step and must be
+ *     destroyed or have its state restored from a checkpoint.
  *   - def_step / def_a_step / def_output only enqueue work on the context's
  *     stream and return; they never synchronise with the device.
  *   - A context is not thread-safe; use one context per host thread.
@@ -119,7 +126,11 @@ int def_a_step(def_ctx *ctx, const float *grads, uint64_t ld);
  *              on the device: a table seen before costs nothing, a new one is
  *              copied to the device with a blocking copy (and, once four are held,
  *              after a stream synchronisation, since the one it replaces may be
- *              in use).
+ *              in use).  While the stream is being captured into a HIP graph only
+ *              a table that is already on the device is accepted (DEF_EINVAL
+ *              otherwise: run one eager step with it first), and a table used under
+ *              capture stays on the device, unchanged, until def_destroy, because
+ *              every replay reads it.
  *   y_out      as in def_step (one flat vector of d floats) or NULL.
  * Works with either parameter mode.
  */
@@ -178,8 +189,11 @@ int def_output(def_ctx *ctx, float *y_out);
  *                 w_out[k*ldw + i] = x_{t+1}[i] - lambda * e_{k,t+1}[i]
  *                 for all workers k and indices i.  w_out: DEVICE, [W][ldw] floats,
  *                 ldw >= d, caller-owned, must stay valid while set.
- *                 w_out == NULL switches it off.  Before the first step the
- *                 points are x_0 itself (e_{k,0} = 0).
+ *                 w_out == NULL switches it off.  The call itself writes the
+ *                 points of the current state (as def_detach does), so w_out is
+ *                 valid at once: before the first step it holds x_0 in every row
+ *                 (e_{k,0} = 0).  Not allowed between def_pack and def_apply
+ *                 (DEF_EINVAL).
  * def_detach      writes the same quantity for the CURRENT state (after a restore,
  *                 or with another lambda) without stepping.
  * DEF_EINVAL for lambda outside [0, 1], ldw < d, or a misaligned pointer.
@@ -199,6 +213,30 @@ int def_detach(def_ctx *ctx, float *w_out, uint64_t ldw, float lambda);
  * from run to run (no atomics).  DEF_EINVAL for lambda outside [0, 1].
  */
 int def_diagnostics(def_ctx *ctx, float lambda, double *out);
+
+/*
+ * The same per worker (Sec. 3.2, item (1); Appendix A, first display): for
+ * k = 0..W-1, with e_t = (1/W) sum_k e_k,
+ *   out[k]       = ||e_k||^2
+ *   out[W + k]   = <e_t, e_k>
+ *   out[2W + k]  = lambda*(k,t) = <e_t, e_k> / ||e_k||^2   (0 if e_k = 0): the lambda at
+ *                  which worker k's point x - lambda*e_k is closest to y_t.
+ * out: DEVICE, 3*W doubles, 8-byte aligned.  Asynchronous; float64 sums in a fixed
+ * order (no atomics).  (1/W) sum_k out[W + k] equals def_diagnostics' out[0].
+ */
+int def_diagnostics_workers(def_ctx *ctx, double *out);
+
+/*
+ * Where def_step / def_a_step (and their tensor forms) form the cross-worker average
+ * (Algorithm 1, all-reduce and update lines).
+ *   on != 0 (default)  inside the streaming launch: the wave that stores the last kept
+ *                      element of a 256-column piece of the block adds that piece over
+ *                      the workers (k = 0..W-1 in order) and updates x there; a step is
+ *                      one kernel launch.
+ *   on == 0            in a second launch after the streaming pass (LDS-staged rows).
+ * Both give bit-identical results.  def_pack / def_apply always use separate launches.
+ */
+int def_set_fused_average(def_ctx *ctx, int on);
 
 /* Replace the seed (Sec. 1: the seed all workers share).  t keeps counting. */
 int def_set_seed(def_ctx *ctx, uint64_t seed);
@@ -249,6 +287,9 @@ int def_force_next_start(def_ctx *ctx, int64_t s);
 
 /* Start index and length B of the block kept by the most recent step. */
 int def_last_block(const def_ctx *ctx, uint64_t *start, uint64_t *len);
+
+/* Block length B = ceil(d/R) of this context (delta = B/d, Assumption 4.2). */
+int def_block_length(const def_ctx *ctx, uint64_t *len);
 
 /*
  * The shared block draw as a pure function (HOST, no GPU needed):

@@ -46,6 +46,9 @@ SIGNATURES = {
     "def_set_detach": (ctypes.c_int, [_vp, _vp, _u64, _f32]),
     "def_detach": (ctypes.c_int, [_vp, _vp, _u64, _f32]),
     "def_diagnostics": (ctypes.c_int, [_vp, _f32, _vp]),
+    "def_diagnostics_workers": (ctypes.c_int, [_vp, _vp]),
+    "def_set_fused_average": (ctypes.c_int, [_vp, ctypes.c_int]),
+    "def_block_length": (ctypes.c_int, [_vp, ctypes.POINTER(_u64)]),
     "def_set_seed": (ctypes.c_int, [_vp, _u64]),
     "def_set_device_draw": (ctypes.c_int, [_vp, ctypes.c_int]),
     "def_sync_step": (ctypes.c_int, [_vp]),
@@ -232,9 +235,14 @@ class DefContext:
                "def_pack_tensors")
         return out.value or 0
 
+    def block_length(self) -> int:
+        n = _u64()
+        _check(self._lib.def_block_length(self._h, ctypes.byref(n)), "def_block_length")
+        return n.value
+
     def block_view(self, ptr: int):
         """torch view [B] of the vector def_pack returned (what a collective would reduce)."""
-        return device_view(ptr, (-(-self.d // self.R),))
+        return device_view(ptr, (self.block_length(),))
 
     def apply(self, block, divisor: float, y_out=None) -> None:
         _check(self._lib.def_apply(self._h, _ptr(block), divisor, _ptr(y_out)), "def_apply")
@@ -253,7 +261,14 @@ class DefContext:
         """out: float64 device tensor with 4 entries (see def_diagnostics)."""
         _check(self._lib.def_diagnostics(self._h, lam, _ptr(out)), "def_diagnostics")
 
+    def diagnostics_workers(self, out) -> None:
+        """out: float64 device tensor with 3*W entries (see def_diagnostics_workers)."""
+        _check(self._lib.def_diagnostics_workers(self._h, _ptr(out)), "def_diagnostics_workers")
+
     # -- knobs ----------------------------------------------------------------
+    def set_fused_average(self, on: bool) -> None:
+        _check(self._lib.def_set_fused_average(self._h, 1 if on else 0), "def_set_fused_average")
+
     def set_seed(self, seed: int) -> None:
         _check(self._lib.def_set_seed(self._h, seed), "def_set_seed")
 
@@ -302,9 +317,8 @@ class DefContext:
         """(e, m, avg_block) as torch views of the library-owned buffers: e and m
         are [W][ld_state] (m is None without momentum), avg_block is [B]."""
         e, m, a, ld = self.state_ptrs()
-        B = -(-self.d // self.R)
         return (device_view(e, (self.W, ld)), device_view(m, (self.W, ld)) if m else None,
-                device_view(a, (B,)))
+                device_view(a, (self.block_length(),)))
 
     # -- timing ---------------------------------------------------------------
     def profile_begin(self, max_steps: int) -> None:

@@ -104,6 +104,9 @@ struct def_ctx {
     // device state owned by the library
     float *e = nullptr, *m = nullptr, *msg = nullptr, *avg = nullptr;
     double *diag = nullptr;   // per-workgroup partial sums of def_diagnostics
+    double *diag_workers = nullptr;   // per-workgroup partial sums of def_diagnostics_workers
+    uint32_t *tile_count = nullptr;   // one counter per DEF_AVG_TILE block columns (fused average)
+    bool fused_average = true;        // def_step folds the average + update into the streaming launch
     DefCtl *ctl = nullptr;    // device copy of (t, seed, forced, s) for the device draw
     bool device_draw = false;
     uint64_t ld = 0, ldmsg = 0;
@@ -123,8 +126,9 @@ struct def_ctx {
         std::vector<const float *> host;
         const float **dev = nullptr;
         uint64_t last_used = 0;
+        bool captured = false;        // a captured graph reads this table: never replaced
     };
-    GradTable gtab[DEF_GRAD_TABLES];
+    std::vector<GradTable> gtab;
     uint64_t gtab_clock = 0;
     // per-launch timing of the streaming kernel
     std::vector<hipEvent_t> ev;
@@ -143,6 +147,8 @@ void free_ctx(def_ctx *c)
     (void)hipFree(c->msg);
     (void)hipFree(c->avg);
     (void)hipFree(c->diag);
+    (void)hipFree(c->diag_workers);
+    (void)hipFree(c->tile_count);
     (void)hipFree(c->ctl);
     (void)hipFree(c->d_off);
     (void)hipFree(c->d_tile_tensor);
@@ -158,6 +164,7 @@ DefStepArgs base_args(const def_ctx *c, uint64_t s)
     a.lr = c->lr; a.mu = c->mu; a.wd = c->wd;
     a.e = c->e; a.m = c->m; a.ld = c->ld;
     a.msg = c->msg; a.ldmsg = c->ldmsg; a.avg = c->avg;
+    a.tile_count = nullptr;
     a.x_flat = c->x_flat; a.x_ptrs = c->d_xptrs; a.off = c->d_off; a.L = c->L;
     a.tile_tensor = c->d_tile_tensor;
     a.w = c->w; a.ldw = c->ldw; a.lam = c->lam;
@@ -176,7 +183,16 @@ int run_stream(def_ctx *c, DefStepArgs &a)
     }
     const bool prof = c->prof_n < c->prof_cap;
     if (prof) DEF_HIP(hipEventRecord(c->ev[2 * c->prof_n], c->stream));
-    DEF_HIP(def_launch_stream(a, c->stream));
+    {
+        const hipError_t err = def_launch_stream(a, c->stream);
+        if (err != hipSuccess) {
+            // the draw kernel is already enqueued and will advance the device's step counter;
+            // put the device copy back to the host's (t, forced start), which have not moved
+            if (c->device_draw)
+                (void)def_launch_ctl_set(c->ctl, DEF_CTL_T | DEF_CTL_FORCED, c->t, 0, c->forced, c->stream);
+            return hip_fail(err);
+        }
+    }
     if (prof) {
         DEF_HIP(hipEventRecord(c->ev[2 * c->prof_n + 1], c->stream));
         ++c->prof_n;
@@ -194,9 +210,10 @@ int run_stream(def_ctx *c, DefStepArgs &a)
 // The sequence of one iteration: streaming pass, average + update, optional y.
 int run_step(def_ctx *c, DefStepArgs &a, float *y_out)
 {
+    if (c->fused_average) a.tile_count = c->tile_count;
     const int rc = run_stream(c, a);
     if (rc != DEF_OK) return rc;
-    DEF_HIP(def_launch_average_update(a, c->stream));
+    if (!a.tile_count) DEF_HIP(def_launch_average_update(a, c->stream));
     if (y_out) DEF_HIP(def_launch_output(a, y_out, c->stream));
     return DEF_OK;
 }
@@ -219,30 +236,48 @@ uint64_t next_start(const def_ctx *c)
 
 // The device copy of a table of W*L gradient pointers: one of the cached tables if the same
 // pointers were seen recently, else uploaded into a free or the least recently used slot.
+// While the stream is being captured nothing may be copied, and what the captured launch
+// reads must stay as it is for every replay: a table that is not on the device yet is
+// refused, and one that was used under capture is never replaced afterwards.
 int device_grad_table(def_ctx *ctx, const float *const *grad_ptrs, const float ***out)
 {
     const size_t n = (size_t)ctx->W * ctx->L;
     for (size_t q = 0; q < n; ++q)
         if (!grad_ptrs[q] || (uintptr_t)grad_ptrs[q] % 4 != 0) return DEF_EINVAL;
-    def_ctx::GradTable *use = nullptr, *free_slot = nullptr, *oldest = nullptr;
+    hipStreamCaptureStatus capture = hipStreamCaptureStatusNone;
+    DEF_HIP(hipStreamIsCapturing(ctx->stream, &capture));
+    const bool capturing = capture != hipStreamCaptureStatusNone;
+    def_ctx::GradTable *use = nullptr, *oldest = nullptr;
+    size_t replaceable = 0;
     for (auto &tb : ctx->gtab) {
-        if (!tb.dev) {
-            if (!free_slot) free_slot = &tb;
-        } else if (tb.host.size() == n &&
-                   std::memcmp(tb.host.data(), grad_ptrs, n * sizeof(float *)) == 0) {
+        if (tb.host.size() == n && std::memcmp(tb.host.data(), grad_ptrs, n * sizeof(float *)) == 0) {
             use = &tb;
             break;
-        } else if (!oldest || tb.last_used < oldest->last_used) {
-            oldest = &tb;
+        }
+        if (!tb.captured) {
+            ++replaceable;
+            if (!oldest || tb.last_used < oldest->last_used) oldest = &tb;
         }
     }
     if (!use) {
-        def_ctx::GradTable *slot = free_slot ? free_slot : oldest;
-        if (!slot->dev) {
-            DEF_HIP(hipMalloc((void **)&slot->dev, n * sizeof(float *)));
-        } else {
+        if (capturing) return DEF_EINVAL;      // run one eager step with this table first
+        def_ctx::GradTable *slot = nullptr;
+        if (replaceable >= DEF_GRAD_TABLES) {
+            slot = oldest;
             // a step in flight may still read the table that is being replaced
             DEF_HIP(hipStreamSynchronize(ctx->stream));
+        } else {
+            try {
+                ctx->gtab.emplace_back();
+            } catch (const std::bad_alloc &) {
+                return DEF_ENOMEM;
+            }
+            slot = &ctx->gtab.back();
+            const hipError_t err = hipMalloc((void **)&slot->dev, n * sizeof(float *));
+            if (err != hipSuccess) {
+                ctx->gtab.pop_back();
+                return hip_fail(err);
+            }
         }
         slot->host.clear();                    // not a valid match until the copy has succeeded
         DEF_HIP(hipMemcpy(slot->dev, grad_ptrs, n * sizeof(float *), hipMemcpyHostToDevice));
@@ -254,6 +289,7 @@ int device_grad_table(def_ctx *ctx, const float *const *grad_ptrs, const float *
         use = slot;
     }
     use->last_used = ++ctx->gtab_clock;
+    if (capturing) use->captured = true;
     *out = use->dev;
     return DEF_OK;
 }
@@ -327,6 +363,11 @@ int def_init(def_ctx **out, const def_config *cfg)
     DEF_INIT_HIP(hipMalloc((void **)&c->msg, msg_bytes));
     DEF_INIT_HIP(hipMalloc((void **)&c->avg, c->ldmsg * sizeof(float)));
     DEF_INIT_HIP(hipMalloc((void **)&c->diag, def_diag_blocks(c->d) * 2 * sizeof(double)));
+    DEF_INIT_HIP(hipMalloc((void **)&c->diag_workers,
+                           def_diag_worker_blocks(c->d) * 2 * (size_t)c->W * sizeof(double)));
+    const size_t count_bytes = c->ldmsg / DEF_AVG_TILE * sizeof(uint32_t);
+    DEF_INIT_HIP(hipMalloc((void **)&c->tile_count, count_bytes));
+    DEF_INIT_HIP(hipMemsetAsync(c->tile_count, 0, count_bytes, c->stream));
     DEF_INIT_HIP(hipMalloc((void **)&c->ctl, sizeof(DefCtl)));
     DEF_INIT_HIP(hipMemsetAsync(c->ctl, 0, sizeof(DefCtl), c->stream));
 
@@ -467,10 +508,18 @@ int def_output(def_ctx *ctx, float *y_out)
 
 int def_set_detach(def_ctx *ctx, float *w_out, uint64_t ldw, float lambda)
 {
-    if (!ctx) return DEF_EINVAL;
+    // between def_pack and def_apply the off-block points of the step in flight are already
+    // written (or not): changing the destination there would leave them half done
+    if (!ctx || ctx->pending_apply) return DEF_EINVAL;
     if (w_out) {
         if ((uintptr_t)w_out % 4 != 0 || ldw < ctx->d || !(lambda >= 0.0f && lambda <= 1.0f))
             return DEF_EINVAL;
+        DEF_ON_DEVICE(ctx);
+        // the points for the state as it is now (x_0 itself before the first step), so that
+        // the buffer is valid from this call on and not only after the next step
+        DefStepArgs a = base_args(ctx, 0);
+        a.w = w_out; a.ldw = ldw; a.lam = lambda;
+        DEF_HIP(def_launch_detach(a, ctx->stream));
         ctx->w = w_out; ctx->ldw = ldw; ctx->lam = lambda;
     } else {
         ctx->w = nullptr; ctx->ldw = 0; ctx->lam = 0.0f;
@@ -496,6 +545,22 @@ int def_diagnostics(def_ctx *ctx, float lambda, double *out)
     DEF_ON_DEVICE(ctx);
     DefStepArgs a = base_args(ctx, 0);
     DEF_HIP(def_launch_diagnostics(a, lambda, ctx->diag, out, ctx->stream));
+    return DEF_OK;
+}
+
+int def_diagnostics_workers(def_ctx *ctx, double *out)
+{
+    if (!ctx || !out || (uintptr_t)out % 8 != 0) return DEF_EINVAL;
+    DEF_ON_DEVICE(ctx);
+    DefStepArgs a = base_args(ctx, 0);
+    DEF_HIP(def_launch_diagnostics_workers(a, ctx->diag_workers, out, ctx->stream));
+    return DEF_OK;
+}
+
+int def_set_fused_average(def_ctx *ctx, int on)
+{
+    if (!ctx) return DEF_EINVAL;
+    ctx->fused_average = on != 0;
     return DEF_OK;
 }
 
@@ -576,6 +641,13 @@ int def_last_block(const def_ctx *ctx, uint64_t *start, uint64_t *len)
     if (!ctx || !ctx->has_last) return DEF_EINVAL;
     if (start) *start = ctx->last_start;
     if (len) *len = ctx->B;
+    return DEF_OK;
+}
+
+int def_block_length(const def_ctx *ctx, uint64_t *len)
+{
+    if (!ctx || !len) return DEF_EINVAL;
+    *len = ctx->B;
     return DEF_OK;
 }
 

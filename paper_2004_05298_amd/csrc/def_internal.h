@@ -78,6 +78,9 @@ struct DefStepArgs {
     float *msg;        // [W][ldmsg] compact compressed vectors C(p_k): entry j <-> index (s+j) mod d
     uint64_t ldmsg;    // multiple of DEF_AVG_TILE
     float *avg;        // [B] averaged block
+    // not null: the streaming pass itself averages the kept block and updates x (one counter
+    // per DEF_AVG_TILE block columns, all zero between steps); null: a second kernel does
+    uint32_t *tile_count;
     // parameters x
     float *x_flat;             // flat mode, else nullptr
     float *const *x_ptrs;      // DEVICE table of L tensor pointers (tensor mode), else nullptr
@@ -122,3 +125,7 @@ hipError_t def_launch_diagnostics(const DefStepArgs &a, float lambda, double *pa
                                   hipStream_t st);
 // w_k = x - lambda*e_k for the current state (a.w, a.ldw, a.lam).
 hipError_t def_launch_detach(const DefStepArgs &a, hipStream_t st);
+// Per-worker statistics ||e_k||^2, <e_t, e_k> and their ratio lambda*(k,t), as 3*W doubles in out.
+// partials: def_diag_worker_blocks(d) * 2 * W doubles.
+uint64_t def_diag_worker_blocks(uint64_t d);
+hipError_t def_launch_diagnostics_workers(const DefStepArgs &a, double *partials, double *out, hipStream_t st);

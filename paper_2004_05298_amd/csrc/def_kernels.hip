@@ -128,6 +128,10 @@ __device__ __forceinline__ bool decode_item(uint64_t total, uint64_t tiles, uint
     return true;
 }
 
+// Defined with the averaging kernels below: counts the kept elements a wave has just
+// stored, and averages every tile of the compact block that this wave completed.
+__device__ __forceinline__ void finish_block_tiles(const DefStepArgs &a, uint64_t j0, uint32_t kept);
+
 // ---------------------------------------------------------------------------
 // Streaming pass.  One workgroup = one worker's tile of THREADS*U float4 groups;
 // thread t owns groups t, t+THREADS, ... so that each wave instruction touches
@@ -241,9 +245,13 @@ __global__ __launch_bounds__(THREADS) void def_stream_vec4_kernel(DefStepArgs a,
         }
     }
 
+    uint32_t kept_of[U];                                      // bit c: element c of group u was kept
+    uint64_t j0_of[U];                                        // block position of the group's first element
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         const uint64_t i = i_first + u * STRIDE;
+        kept_of[u] = 0;
+        j0_of[u] = 0;
         if (!interior && i >= a.d) continue;
         v4f p;
 #pragma unroll
@@ -256,6 +264,7 @@ __global__ __launch_bounds__(THREADS) void def_stream_vec4_kernel(DefStepArgs a,
         // position of element i inside the circular block: j = (i - s) mod d
         uint64_t j0 = i >= s ? i - s : i + a.d - s;
         v4f en = p;                                           // off-block: e <- p
+        uint32_t kept = 0;                                    // bit c: element i + c is in the block
         if (!(j0 >= a.B && j0 + 3 < a.d)) {                   // some element may be kept
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
@@ -264,9 +273,12 @@ __global__ __launch_bounds__(THREADS) void def_stream_vec4_kernel(DefStepArgs a,
                 if (i + c < a.d && j < a.B) {
                     msg[j] = p[c];                            // C(p_k), compact
                     en[c] = 0.0f;                             // p - C(p) = +0 inside the block
+                    kept |= 1u << c;
                 }
             }
         }
+        kept_of[u] = kept;
+        j0_of[u] = j0;
         if constexpr (HAS_MU) store4<NT_ST>(m + i, mv[u]);
         store4<NT_ST>(e + i, en);
         if constexpr (HAS_DT) {
@@ -287,6 +299,12 @@ __global__ __launch_bounds__(THREADS) void def_stream_vec4_kernel(DefStepArgs a,
                     if (i + c < a.d) w[i + c] = wv[c];
             }
         }
+    }
+    if (a.tile_count) {
+        // all lanes of the wave are here again (those beyond d hold no element: kept == 0)
+        static_assert(THREADS == 64, "the fused average is written for one-wave workgroups");
+#pragma unroll
+        for (int u = 0; u < U; ++u) finish_block_tiles(a, j0_of[u], kept_of[u]);
     }
 }
 
@@ -348,6 +366,79 @@ __device__ __forceinline__ void apply_block_entry(const DefStepArgs &a, uint64_t
         const float scaled = a.lam * 0.0f;
         const float wv = x_new - scaled;
         for (uint32_t k = 0; k < a.W; ++k) a.w[(uint64_t)k * a.ldw + i] = wv;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// The same average and update, folded into the streaming launch (no second kernel, no
+// gap between two launches).  Every wave of the streaming pass that kept elements adds,
+// per tile of DEF_AVG_TILE block columns it touched, the number of elements it stored to
+// that tile's counter in device memory; a tile is complete when its counter reaches
+// W * (columns of the tile), and the wave whose addition completes it sums the W staged
+// rows of that tile in worker order from +0 (the same sum as the kernel above), updates
+// x there and leaves the counter at zero for the next step.  Nobody waits for anybody:
+// every wave adds and leaves, so the grid always drains.  Release/acquire fences of
+// device scope around the counter make the other waves' stores visible (they may have
+// run on another XCD, whose L2 is a different one).
+// Who reads x[i] for an index inside the block (weight decay, detached points) is a wave
+// that also keeps element i, so it has finished its loads before it adds to the counter,
+// hence before x[i] changes.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ void average_block_tile(const DefStepArgs &a, uint32_t tile)
+{
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint64_t j = (uint64_t)tile * DEF_AVG_TILE + lane * 4;
+    v4f acc = (v4f)(0.0f);
+    for (uint32_t k = 0; k < a.W; ++k)
+        acc = acc + load4<false>(a.msg + (uint64_t)k * a.ldmsg + j);      // rows padded to the tile
+    const v4f cbar = acc / (float)a.W;                                      // (1/W) sum_k C(p_k)
+#pragma unroll
+    for (int c = 0; c < 4; ++c)
+        if (j + c < a.B) apply_block_entry(a, j + c, cbar[c]);
+}
+
+__device__ __forceinline__ void finish_block_tiles(const DefStepArgs &a, uint64_t j0, uint32_t kept)
+{
+    if (__ballot(kept != 0) == 0) return;                   // the wave kept nothing (nearly all waves)
+    __threadfence();                                        // release: this wave's msg stores first
+    const uint32_t lane = threadIdx.x & 63u;
+    uint32_t tile_of[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        uint64_t j = j0 + c;
+        if (j >= a.d) j -= a.d;
+        tile_of[c] = (uint32_t)(j / DEF_AVG_TILE);
+    }
+    // the wave's kept elements lie in at most a few tiles; take them one tile at a time
+    for (;;) {
+        const uint64_t waiting = __ballot(kept != 0);
+        if (waiting == 0) break;
+        uint32_t mine = 0;
+#pragma unroll
+        for (int c = 3; c >= 0; --c)
+            if (kept >> c & 1u) mine = tile_of[c];          // tile of this lane's first waiting element
+        const uint32_t tile = __shfl(mine, __ffsll((unsigned long long)waiting) - 1, 64);
+        uint32_t n = 0;
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+            if ((kept >> c & 1u) && tile_of[c] == tile) {
+                ++n;
+                kept &= ~(1u << c);
+            }
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) n += __shfl_xor(n, off, 64);      // wave total
+        uint32_t before = 0;
+        if (lane == 0)
+            before = __hip_atomic_fetch_add(a.tile_count + tile, n, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        before = __shfl(before, 0, 64);
+        const uint64_t first_col = (uint64_t)tile * DEF_AVG_TILE;
+        const uint64_t cols = a.B - first_col < DEF_AVG_TILE ? a.B - first_col : DEF_AVG_TILE;
+        if ((uint64_t)before + n == cols * a.W) {           // this wave completed the tile
+            __threadfence();                                // acquire: the other waves' msg stores
+            if (lane == 0)
+                __hip_atomic_store(a.tile_count + tile, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            average_block_tile(a, tile);
+        }
     }
 }
 
@@ -525,6 +616,89 @@ __global__ __launch_bounds__(DEF_THREADS) void def_diag_final_kernel(const doubl
 }
 
 // ---------------------------------------------------------------------------
+// Per-worker statistics (Sec. 3.2, item (1); Appendix A, first display), float64:
+//   ||e_k||^2 and <e_t, e_k> for every worker k, whose ratio lambda*(k,t) is the
+//   lambda that brings worker k's evaluation point x - lambda*e_k closest to y.
+// One launch covers DIAG_KC workers k0..k0+DIAG_KC-1: a thread walks all W workers of
+// its four columns in order to form e_t there (keeping the values of the launch's own
+// workers in registers), then adds the products to 2*DIAG_KC running sums; it strides
+// over the columns with the whole grid.  The workgroup adds its threads' sums and writes
+// one row of partials; a second kernel adds the rows in a fixed order.  No atomics.
+// ---------------------------------------------------------------------------
+constexpr int DIAG_KC = 16;
+constexpr uint32_t DIAG_WORKER_BLOCKS = 1024;
+
+__global__ __launch_bounds__(DEF_THREADS) void def_diag_workers_partial_kernel(DefStepArgs a, uint32_t k0,
+                                                                               double *partials)
+{
+    __shared__ double lds[DEF_THREADS / 64];
+    double nrm[DIAG_KC], inn[DIAG_KC];
+#pragma unroll
+    for (int q = 0; q < DIAG_KC; ++q) nrm[q] = inn[q] = 0.0;
+    const uint32_t k_end = min(a.W, k0 + (uint32_t)DIAG_KC);
+    const uint64_t stride = (uint64_t)gridDim.x * DEF_THREADS * 4;
+    for (uint64_t i = ((uint64_t)blockIdx.x * DEF_THREADS + threadIdx.x) * 4; i < a.d; i += stride) {
+        double acc[4] = {0.0, 0.0, 0.0, 0.0};
+        v4f own[DIAG_KC];
+        for (uint32_t k = 0; k < k0; ++k) {
+            const v4f ev = load4<false>(a.e + (uint64_t)k * a.ld + i);      // padding columns hold zeros
+#pragma unroll
+            for (int c = 0; c < 4; ++c) acc[c] += (double)ev[c];
+        }
+#pragma unroll
+        for (int q = 0; q < DIAG_KC; ++q) {
+            own[q] = (v4f)(0.0f);
+            if (k0 + q < k_end) {
+                own[q] = load4<false>(a.e + (uint64_t)(k0 + q) * a.ld + i);
+#pragma unroll
+                for (int c = 0; c < 4; ++c) acc[c] += (double)own[q][c];
+            }
+        }
+        for (uint32_t k = k_end; k < a.W; ++k) {
+            const v4f ev = load4<false>(a.e + (uint64_t)k * a.ld + i);
+#pragma unroll
+            for (int c = 0; c < 4; ++c) acc[c] += (double)ev[c];
+        }
+        double mean[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) mean[c] = acc[c] / (double)a.W;         // e_t
+#pragma unroll
+        for (int q = 0; q < DIAG_KC; ++q)
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const double v = (double)own[q][c];
+                nrm[q] += v * v;
+                inn[q] += mean[c] * v;
+            }
+    }
+    double *row = partials + (uint64_t)blockIdx.x * 2 * a.W;
+#pragma unroll
+    for (int q = 0; q < DIAG_KC; ++q) {
+        const double bn = block_sum(nrm[q], lds);
+        const double bi = block_sum(inn[q], lds);
+        if (threadIdx.x == 0 && k0 + q < k_end) {
+            row[k0 + q] = bn;
+            row[a.W + k0 + q] = bi;
+        }
+    }
+}
+
+__global__ __launch_bounds__(DEF_THREADS) void def_diag_workers_final_kernel(const double *partials, uint32_t rows,
+                                                                             uint32_t W, double *out)
+{
+    for (uint32_t q = threadIdx.x; q < 2 * W; q += DEF_THREADS) {
+        double sum = 0.0;
+        for (uint32_t r = 0; r < rows; ++r) sum += partials[(uint64_t)r * 2 * W + q];
+        out[q] = sum;                                       // out[k] = ||e_k||^2, out[W+k] = <e_t, e_k>
+    }
+    __syncthreads();
+    for (uint32_t k = threadIdx.x; k < W; k += DEF_THREADS) {
+        const double n = out[k], in = out[W + k];
+        out[2 * W + k] = n > 0.0 ? in / n : 0.0;            // lambda*(k,t)
+    }
+}
+
+// ---------------------------------------------------------------------------
 // Block draw on the device (Sec. 1: one uniformly sampled start index, same seed
 // for all workers).  Philox4x64-10 (Salmon et al., SC 2011) with counter (t,0,0,0)
 // and key (seed,0); the first output word mod d.
@@ -591,9 +765,10 @@ void def_describe_stream_kernel(const DefStepArgs &a, char *out, size_t cap)
     if (reads_x) std::snprintf(order, sizeof order, "blocked:%u", DEF_SUPER_TILES);
     else std::snprintf(order, sizeof order, "linear");
     std::snprintf(out, cap,
-                  "def_stream_vec4_kernel<mu=%d,wd=%d,detach=%d,tables=%d,threads=%u,quads=%u,nt=%d,order=%s,lds=%u>",
+                  "def_stream_vec4_kernel<mu=%d,wd=%d,detach=%d,tables=%d,threads=%u,quads=%u,nt=%d,order=%s,lds=%u,"
+                  "average=%s>",
                   mu, wd, dt, tables, DEF_VEC_THREADS, DEF_VEC_QUADS, (int)streams_non_temporal(a), order,
-                  def_stream_lds_reserve(mu, dt, streams_non_temporal(a)));
+                  def_stream_lds_reserve(mu, dt, streams_non_temporal(a)), a.tile_count ? "fused" : "separate");
 }
 
 // Picks the instantiation for (momentum, weight decay, detached points).  Whenever x
@@ -706,6 +881,24 @@ hipError_t def_launch_diagnostics(const DefStepArgs &a, float lambda, double *pa
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
     def_diag_final_kernel<<<dim3(1), dim3(DEF_THREADS), 0, st>>>(partials, blocks, a.W, lambda, out);
+    return hipGetLastError();
+}
+
+uint64_t def_diag_worker_blocks(uint64_t d)
+{
+    const uint64_t need = def_diag_blocks(d);
+    return need < DIAG_WORKER_BLOCKS ? need : DIAG_WORKER_BLOCKS;
+}
+
+hipError_t def_launch_diagnostics_workers(const DefStepArgs &a, double *partials, double *out, hipStream_t st)
+{
+    const uint32_t rows = (uint32_t)def_diag_worker_blocks(a.d);
+    for (uint32_t k0 = 0; k0 < a.W; k0 += DIAG_KC) {
+        def_diag_workers_partial_kernel<<<dim3(rows), dim3(DEF_THREADS), 0, st>>>(a, k0, partials);
+        const hipError_t err = hipGetLastError();
+        if (err != hipSuccess) return err;
+    }
+    def_diag_workers_final_kernel<<<dim3(1), dim3(DEF_THREADS), 0, st>>>(partials, rows, a.W, out);
     return hipGetLastError();
 }
 

@@ -85,35 +85,25 @@ def test_detached_distance_is_smaller_at_lambda_star():
     assert 0.0 < dg["lam_star"] < 1.0
 
 
-@pytest.mark.gpu
-@pytest.mark.parametrize("name", list(METHODS))
-@pytest.mark.parametrize("mu", [0.5, 0.0])
-def test_gpu_closed_loop_reproduces_oracle(name, mu):
-    torch = pytest.importorskip("torch")
-    if not torch.cuda.is_available():
-        pytest.skip("no GPU")
+def _gpu_run(torch, prob, R, lam, T, lr0, mu, want_w=True):
+    """The closed loop on the GPU: gradients formed by element-wise torch ops from the
+    library's own detached points.  Returns numpy copies of (x, e, y, w)."""
     from paper_2004_05298_amd import binding, workloads as wl
     binding.load_library()
-    torch.cuda.set_device(0)
     dev = torch.device("cuda:0")
-    R, lam = METHODS[name]
-    prob = ToyProblem(d=50003, W=4, seed=4)
-    d, W, T, lr0 = prob.d, prob.W, 40, 0.2
+    d, W = prob.d, prob.W
     ld = wl.padded_ld(d)
-    ora, curve = oracle_run(prob, R, lam, T, lr0, mu)
-
     x = torch.from_numpy(prob.x0).to(dev)
     a = torch.from_numpy(prob.a).to(dev)
     c = torch.from_numpy(prob.c).to(dev)
     noise = torch.from_numpy(prob.noise).to(dev)
     g = torch.zeros((W, ld), dtype=torch.float32, device=dev)
-    w = torch.zeros((W, ld), dtype=torch.float32, device=dev)
-    w[:, :d] = x                                     # e_{k,0} = 0: the first points are x_0
+    w = torch.full((W, ld), float("nan"), dtype=torch.float32, device=dev)
     y = torch.empty(d, dtype=torch.float32, device=dev)
     ctx = binding.DefContext(d, W, R, lr0, mu, 0.0, 77, params=x,
                              stream=torch.cuda.current_stream().cuda_stream)
     try:
-        ctx.set_detach(w, ld, lam)
+        ctx.set_detach(w, ld, lam)                   # also writes the first points: x_0 (e_{k,0} = 0)
         for t in range(T):
             ctx.set_lr(schedule(t, T, lr0))
             gv = g[:, :d]
@@ -124,14 +114,59 @@ def test_gpu_closed_loop_reproduces_oracle(name, mu):
         torch.cuda.synchronize()
         assert ctx.last_path_flat()
         e, m, _ = ctx.state_tensors()
-        xg, yg = x.cpu().numpy(), y.cpu().numpy()
-        assert np.array_equal(xg.view(np.uint32), ora.x.view(np.uint32))
-        assert np.array_equal(e.cpu().numpy()[:, :d].view(np.uint32), ora.e.view(np.uint32))
-        assert np.array_equal(yg.view(np.uint32), ora.y().view(np.uint32))
-        assert np.array_equal(w.cpu().numpy()[:, :d].view(np.uint32),
-                              ora.detached_points(lam).view(np.uint32))
-        assert prob.objective(yg) == curve[-1][0] and prob.objective(xg) == curve[-1][1]
-        print(f"[closed loop] {name} mu={mu}: F(y_T)={curve[-1][0]:.5f} F(x_T)={curve[-1][1]:.5f} "
-              f"F(x_0)={prob.objective(prob.x0):.5f} min={prob.minimum():.5f}", flush=True)
+        return x.cpu().numpy(), e.cpu().numpy()[:, :d], y.cpu().numpy(), w.cpu().numpy()[:, :d]
     finally:
         ctx.destroy()
+
+
+def _same_bits(a, b):
+    return np.array_equal(a.view(np.uint32), b.view(np.uint32))
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("name", list(METHODS))
+@pytest.mark.parametrize("mu,lr0", [(0.5, 0.2), (0.0, 0.2), (0.9, 0.05)])
+def test_gpu_closed_loop_reproduces_oracle(name, mu, lr0):
+    """mu = 0.9 is the momentum of the paper's experiments (Sec. 5 "Settings")."""
+    torch = pytest.importorskip("torch")
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    torch.cuda.set_device(0)
+    R, lam = METHODS[name]
+    prob = ToyProblem(d=50003, W=4, seed=4)
+    T = 40
+    ora, curve = oracle_run(prob, R, lam, T, lr0, mu)
+    xg, eg, yg, wg = _gpu_run(torch, prob, R, lam, T, lr0, mu)
+    assert _same_bits(xg, ora.x) and _same_bits(eg, ora.e) and _same_bits(yg, ora.y())
+    assert _same_bits(wg, ora.detached_points(lam))
+    assert prob.objective(yg) == curve[-1][0] and prob.objective(xg) == curve[-1][1]
+    print(f"[closed loop] {name} mu={mu}: F(y_T)={curve[-1][0]:.5f} F(x_T)={curve[-1][1]:.5f} "
+          f"F(x_0)={prob.objective(prob.x0):.5f} min={prob.minimum():.5f}", flush=True)
+
+
+@pytest.mark.gpu
+def test_gpu_single_worker_lambda_one_follows_sgd():
+    """K = 1, lambda = 1 on the GPU (Sec. 3.2, text after Eq. (8)): the gradient is taken
+    at x - e = y, so {y_t} is the uncompressed SGD path whatever the compressor drops.
+    The R = 8 run reproduces the oracle bit for bit, and its y agrees with the y (= x) of
+    an R = 1 run fed the same noise; those two differ in where binary32 rounds (x - e is
+    rounded once more than x alone), so they are compared to 2e-5, the bound the oracle's
+    own pin of this identity uses, not bit for bit."""
+    torch = pytest.importorskip("torch")
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    torch.cuda.set_device(0)
+    prob = ToyProblem(d=50003, W=1, seed=4)
+    T, lr0, mu = 40, 0.2, 0.0
+    runs = {}
+    for R in (1, 8):
+        ora, _ = oracle_run(prob, R, 1.0, T, lr0, mu, W=1)
+        xg, eg, yg, wg = _gpu_run(torch, prob, R, 1.0, T, lr0, mu)
+        assert _same_bits(xg, ora.x) and _same_bits(eg, ora.e) and _same_bits(yg, ora.y())
+        assert _same_bits(wg, ora.detached_points(1.0))
+        runs[R] = (xg, eg, yg, wg)
+    assert not runs[1][1].any() and _same_bits(runs[1][2], runs[1][0])      # R = 1: e = 0, y = x
+    assert np.abs(runs[8][1]).max() > 1e-3                                   # R = 8 did drop something
+    assert _same_bits(runs[8][3][0], runs[8][2])                             # w_0 = x - 1*e_0 is y itself
+    scale = float(np.abs(runs[1][2]).max())
+    assert np.abs(runs[8][2].astype(np.float64) - runs[1][2]).max() <= 2e-5 * scale

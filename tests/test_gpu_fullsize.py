@@ -1,12 +1,20 @@
 """GPU parity at the full sizes of the model-shaped configurations, in the launch
 configuration the benchmark times (flat gradients, padded row stride).
 
-The two smaller configurations are compared buffer for buffer with the plain C
-oracle.  For the two largest, the oracle simulates a sample of columns exactly
-(each column of (x, e, m) evolves independently once the block of every step is
-known): random columns plus every tensor boundary, the ends of the vector, and
-the edges of every step's block; whole-buffer properties (zeroing of the last
-block, zero padding) are checked on the device.
+The ResNet-56-, ResNet-18- and ResNet-50-shaped configurations (the last is the
+one the benchmark is quoted on) are compared buffer for buffer with the plain C
+oracle.  For the VGG-16-shaped one, whose oracle state alone would be 53 GB (and
+17.7 GB per gradient set on the host), the oracle simulates a sample of columns
+exactly (each column of (x, e, m) evolves independently once the block of every
+step is known): random columns plus every tensor boundary, the ends of the
+vector, and the edges of every step's block; whole-buffer properties (zeroing of
+the last block, zero padding) are checked on the device.  The sampled check is
+kept for the ResNet-50-shaped configuration as well.
+
+The kernel instantiations that only large problems select (non-temporal accesses
+and the residency cap, several super-tiles of the blocked order) are compared with
+the oracle for every way of calling the step: per-tensor pointers, detached points
+with and without momentum, the stand-alone detach kernel, and the two-halves form.
 """
 from __future__ import annotations
 
@@ -54,9 +62,10 @@ def _gpu_step(ctx, w, t, g, ld, y):
 
 
 @pytest.mark.timeout(600)
-@pytest.mark.parametrize("name", ["resnet56_shaped", "resnet18_shaped"])
+@pytest.mark.parametrize("name", ["resnet56_shaped", "resnet18_shaped", "resnet50_shaped"])
 def test_whole_buffers_against_c_oracle(dev, name):
     w = wl.by_name(name)
+    print(f"[fullsize] {name}: whole buffers, T={w.T}", flush=True)
     d, W, ld = w.d, w.W, wl.padded_ld(w.d)
     x0 = wl.initial_params(w)
     host_pool = wl.gradient_pool(w, ld=ld, threads=16)
@@ -73,6 +82,10 @@ def test_whole_buffers_against_c_oracle(dev, name):
             assert ctx.last_block() == (s, w.B)
         torch.cuda.synchronize()
         assert ctx.last_path_flat()
+        if name != "resnet56_shaped":
+            # large state: the non-temporal, residency-capped instantiation
+            assert "nt=1" in ctx.last_kernel() and "lds=10240" in ctx.last_kernel(), ctx.last_kernel()
+        assert "average=fused" in ctx.last_kernel()
         e, m, avg = ctx.state_tensors()
         e, m, avg = e.cpu().numpy(), m.cpu().numpy(), avg.cpu().numpy()
         xg = x.cpu().numpy()
@@ -213,5 +226,190 @@ def test_sampled_columns_at_full_size(dev, name):
         print(f"[fullsize] {name}: {cols.size} columns, bit-identical x={bit_equal(xg, ora.x)} "
               f"e={bit_equal(eg, ora.e)} m={bit_equal(mg, ora.m)}", flush=True)
         assert bit_equal(eg, ora.e) and bit_equal(mg, ora.m)
+    finally:
+        ctx.destroy()
+
+
+# --------------------------------------------------------------------------- #
+# The instantiations that only large problems select, for every way of calling the
+# step.  Shape: the ResNet-18-shaped model (11.7 M parameters in 62 tensors, 16
+# workers, 748 MB per state buffer: non-temporal accesses, residency cap, three
+# super-tiles of the blocked order), here with weight decay on so that x is read.
+# --------------------------------------------------------------------------- #
+def _large(wd=1e-4, mu=0.9):
+    w = wl.by_name("resnet18_shaped").replace(weight_decay=wd, momentum=mu, T=6, pool=2, variant="def")
+    assert w.d > 3 * 16384 * 256 // 2          # more than one super-tile of 16384 tiles of 256
+    return w
+
+
+def _per_tensor_storage(w, x0, host_pool, dev):
+    """One device range per tensor, each starting at an odd multiple of 4 bytes past a
+    256-byte boundary (pad = l mod 4 floats), for the parameters and for every worker's
+    gradients of every set."""
+    off = [int(v) for v in w.tensor_offsets()]
+    starts, pos = [], 0
+    for l in range(w.n_tensors):
+        pos = -(-pos // 64) * 64 + (l % 4)
+        starts.append(pos)
+        pos += off[l + 1] - off[l]
+    total = pos
+    xbuf = torch.zeros(total, dtype=torch.float32, device=dev)
+    x_host = torch.from_numpy(x0)
+    params = []
+    for l in range(w.n_tensors):
+        view = xbuf[starts[l]:starts[l] + off[l + 1] - off[l]]
+        view.copy_(x_host[off[l]:off[l + 1]])
+        params.append(view)
+    tables = []
+    for g in host_pool:
+        gbuf = torch.zeros((w.W, total), dtype=torch.float32, device=dev)
+        g_dev = torch.from_numpy(g).to(dev)
+        table = []
+        for k in range(w.W):
+            for l in range(w.n_tensors):
+                view = gbuf[k, starts[l]:starts[l] + off[l + 1] - off[l]]
+                view.copy_(g_dev[k, off[l]:off[l + 1]])
+                table.append(view)
+        del g_dev
+        tables.append((gbuf, table))
+    return xbuf, params, tables
+
+
+def _compare_whole_state(ctx, w, x_flat, ora, what):
+    d = w.d
+    e, m, avg = ctx.state_tensors()
+    eg = e.cpu().numpy()
+    assert_close(f"{what}: x", x_flat, ora.x)
+    assert_close(f"{what}: e", eg[:, :d], ora.e)
+    assert np.array_equal(eg[:, :d] == 0, ora.e == 0), f"{what}: zero pattern of e"
+    assert not eg[:, d:].any(), f"{what}: padding of e touched"
+    same = dict(x=bit_equal(x_flat, ora.x), e=bit_equal(eg[:, :d], ora.e))
+    if m is not None:
+        mg = m.cpu().numpy()
+        assert_close(f"{what}: m", mg[:, :d], ora.m)
+        assert not mg[:, d:].any(), f"{what}: padding of m touched"
+        same["m"] = bit_equal(mg[:, :d], ora.m)
+    avg = avg.cpu().numpy()
+    assert_close(f"{what}: averaged block", avg, ora.compact_block())
+    same["avg"] = bit_equal(avg, ora.compact_block())
+    mask = in_block_mask(d, ora.last_start, w.B)
+    assert (bits(eg[:, :d][:, mask]) == 0).all(), f"{what}: last block not zeroed"
+    print(f"[fullsize] {what}: bit-identical {same}", flush=True)
+    assert same["e"] and same.get("m", True), same
+    return same
+
+
+@pytest.mark.timeout(600)
+def test_large_per_tensor_gradients_and_parameters(dev):
+    """def_step_tensors with per-tensor parameters at a size that selects the non-temporal
+    instantiation with pointer tables (Sec. 1: the model is a list of layer tensors, the
+    block runs over their concatenation)."""
+    from paper_2004_05298_amd import binding
+    binding.load_library()
+    w = _large()
+    d, W = w.d, w.W
+    print(f"[fullsize] per-tensor: d={d} W={W} L={w.n_tensors}", flush=True)
+    x0 = wl.initial_params(w)
+    host_pool = wl.gradient_pool(w, ld=d, threads=16)
+    xbuf, params, tables = _per_tensor_storage(w, x0, host_pool, dev)
+    y = torch.empty(d, dtype=torch.float32, device=dev)
+    ora = DefOracleC(x0, W, w.R, w.lr, w.momentum, w.weight_decay, w.seed)
+    ctx = binding.DefContext(d, W, w.R, w.lr, w.momentum, w.weight_decay, w.seed,
+                             param_tensors=params, tensor_offsets=w.tensor_offsets(),
+                             stream=torch.cuda.current_stream().cuda_stream)
+    try:
+        forced = {2: d - w.B // 3}                                     # one block across the end
+        for t in range(w.T):
+            if t in forced:
+                ctx.force_next_start(forced[t])
+            ctx.step_tensors(tables[t % w.pool][1], y if t == w.T - 1 else None)
+            s = ora.step(host_pool[t % w.pool], start=forced.get(t))
+            assert ctx.last_block() == (s, w.B)
+        torch.cuda.synchronize()
+        name = ctx.last_kernel()
+        assert not ctx.last_path_flat()
+        assert "tables=1" in name and "nt=1" in name and "lds=10240" in name and "wd=1" in name, name
+        x_flat = np.concatenate([p.cpu().numpy() for p in params])
+        _compare_whole_state(ctx, w, x_flat, ora, "per-tensor")
+        assert_close("per-tensor: y", y.cpu().numpy(), ora.y())
+    finally:
+        ctx.destroy()
+
+
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("mu", [0.9, 0.0])
+def test_large_detached_points(dev, mu):
+    """def_set_detach(lambda = 0.3) in the same pass, with and without momentum, and the
+    stand-alone def_detach with another lambda, at a size that selects the non-temporal,
+    residency-capped instantiations and several super-tiles (Algorithm 1, "detach" line)."""
+    w = _large(mu=mu)
+    d, W, ld = w.d, w.W, wl.padded_ld(w.d)
+    print(f"[fullsize] detach: d={d} W={W} mu={mu}", flush=True)
+    x0 = wl.initial_params(w)
+    host_pool = wl.gradient_pool(w, ld=ld, threads=16)
+    dev_pool = [torch.from_numpy(g).to(dev) for g in host_pool]
+    x = torch.from_numpy(x0).to(dev)
+    wbuf = torch.full((W, ld), float("nan"), dtype=torch.float32, device=dev)
+    ora = DefOracleC(x0, W, w.R, w.lr, w.momentum, w.weight_decay, w.seed)
+    ctx = _ctx(w, x)
+    try:
+        ctx.set_detach(wbuf, ld, 0.3)
+        torch.cuda.synchronize()
+        assert bit_equal(wbuf[:, :d].cpu().numpy(), ora.detached_points(LAM32)), "w before the first step"
+        forced = {3: d - w.B // 2}
+        for t in range(w.T):
+            if t in forced:
+                ctx.force_next_start(forced[t])
+            ctx.step(dev_pool[t % w.pool], ld, None)
+            s = ora.step(host_pool[t % w.pool], start=forced.get(t))
+            assert ctx.last_block() == (s, w.B)
+            if t in (0, 3, w.T - 1):
+                torch.cuda.synchronize()
+                wg = wbuf[:, :d].cpu().numpy()
+                ref = ora.detached_points(LAM32)
+                assert_close(f"w t={t}", wg, ref)
+                assert bit_equal(wg, ref), f"w t={t} not bit-identical"
+        name = ctx.last_kernel()
+        want_lds = "lds=11520" if mu != 0 else "lds=8960"
+        assert "detach=1" in name and "nt=1" in name and want_lds in name and f"mu={int(mu != 0)}" in name, name
+        assert torch.isnan(wbuf[:, d:]).all(), "the step wrote w past column d"
+        _compare_whole_state(ctx, w, x.cpu().numpy(), ora, f"detach mu={mu}")
+        # stand-alone kernel, another lambda, odd row stride
+        w2 = torch.full((W, d + 3), float("nan"), dtype=torch.float32, device=dev)
+        ctx.detach(w2, d + 3, 0.75)
+        torch.cuda.synchronize()
+        assert bit_equal(w2[:, :d].cpu().numpy(), ora.detached_points(0.75)), "def_detach"
+        assert torch.isnan(w2[:, d:]).all(), "def_detach wrote past column d"
+    finally:
+        ctx.destroy()
+
+
+@pytest.mark.timeout(600)
+def test_large_pack_then_apply(dev):
+    """The two-halves form (def_pack, then def_apply of the local sum with divisor W) at
+    the ResNet-50-shaped size: the same state as def_step, compared with the oracle
+    (Algorithm 1, all-reduce and update lines)."""
+    w = wl.by_name("resnet50_shaped").replace(T=6)
+    d, W, ld = w.d, w.W, wl.padded_ld(w.d)
+    print(f"[fullsize] pack+apply: d={d} W={W}", flush=True)
+    x0 = wl.initial_params(w)
+    host_pool = wl.gradient_pool(w, ld=ld, threads=16)
+    dev_pool = [torch.from_numpy(g).to(dev) for g in host_pool]
+    x = torch.from_numpy(x0).to(dev)
+    y = torch.empty(d, dtype=torch.float32, device=dev)
+    ora = DefOracleC(x0, W, w.R, w.lr, w.momentum, w.weight_decay, w.seed)
+    ctx = _ctx(w, x)
+    try:
+        for t in range(w.T):
+            block = ctx.pack(dev_pool[t % w.pool], ld)
+            assert block == ctx.state_ptrs()[2]
+            ctx.apply(block, float(W), y if t == w.T - 1 else None)
+            s = ora.step(host_pool[t % w.pool])
+            assert ctx.last_block() == (s, w.B)
+        torch.cuda.synchronize()
+        name = ctx.last_kernel()
+        assert "nt=1" in name and "lds=10240" in name and "average=separate" in name, name
+        _compare_whole_state(ctx, w, x.cpu().numpy(), ora, "pack+apply")
+        assert_close("pack+apply: y", y.cpu().numpy(), ora.y())
     finally:
         ctx.destroy()

@@ -120,3 +120,59 @@ def test_graph_replays_follow_the_oracle(dev, steps_per_graph, split):
         _check_state(ctx, x, ora, w.d, "eager after replays")
     finally:
         ctx.destroy()
+
+
+def test_captured_pointer_table_survives_other_tables(dev):
+    """A captured def_step_tensors reads its gradient pointer table from device memory on
+    every replay.  The table must already be on the device when the capture starts (a new
+    one would need a copy, which cannot be captured: DEF_EINVAL), and it must not be
+    replaced when more tables than the library caches pass through afterwards."""
+    from paper_2004_05298_amd import binding
+    stream = torch.cuda.Stream()
+    w, ld, pool, gdev, x, ora, ctx = _setup(dev, stream, T=20)
+    off = [int(v) for v in w.tensor_offsets()]
+
+    def table(buf):
+        return [buf[k, off[l]:off[l + 1]] for k in range(w.W) for l in range(w.n_tensors)]
+
+    try:
+        with torch.cuda.stream(stream):
+            static = torch.zeros_like(gdev[0])
+            others = [g.clone() for g in gdev] + [gdev[0].clone(), gdev[1].clone()]    # six more tables
+        ctx.set_device_draw(True)
+        t = 0
+        with torch.cuda.stream(stream):
+            static.copy_(gdev[0])
+        ctx.step_tensors(table(static))                      # eager: the table goes to the device
+        ora.step(pool[0][:, :w.d]); t += 1
+        stream.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        refused = None
+        with torch.cuda.graph(graph, stream=stream):
+            try:
+                ctx.step_tensors(table(others[0]))           # never seen: cannot be uploaded now
+            except binding.DefError as err:
+                refused = err.status
+            ctx.step_tensors(table(static))
+        assert refused == binding.DEF_EINVAL
+        stream.synchronize()
+        _check_state(ctx, x, ora, w.d, "capture must not execute anything")
+        for replay in range(3):
+            # six other tables eagerly in between: more than the library keeps
+            for q, buf in enumerate(others):
+                src = (t + q) % w.pool
+                with torch.cuda.stream(stream):
+                    buf.copy_(gdev[src])
+                ctx.step_tensors(table(buf))
+                ora.step(pool[src][:, :w.d])
+            t += len(others)
+            with torch.cuda.stream(stream):
+                static.copy_(gdev[t % w.pool])
+                graph.replay()
+            stream.synchronize()
+            ora.step(pool[t % w.pool][:, :w.d]); t += 1
+            _check_state(ctx, x, ora, w.d, f"replay {replay}")
+            ctx.sync_step()
+            assert ctx.get_step() == t
+    finally:
+        ctx.destroy()

@@ -54,10 +54,12 @@ def fetch_avg(ctx):
 def run_case(dev, w, *, weight_decay=None, momentum=None, T=None, flat_params=True,
              mode="flat", misalign=0, ld=None, oracle="np", check_every_step=True,
              with_y=True, special=None, variant=None, forced=None, detach=None, ldw=None,
-             split=False):
+             split=False, fused=None):
     """Run T steps on both sides and compare.  mode: "flat" (one gradient buffer
     [W][ld]) or "tensors" (one allocation per worker and tensor).  split: every
-    iteration is def_pack followed by def_apply of the returned sum with divisor W."""
+    iteration is def_pack followed by def_apply of the returned sum with divisor W.
+    fused: False forms the cross-worker average in a second launch instead of inside
+    the streaming launch (the library's default, None here)."""
     binding = _binding()
     wd = w.weight_decay if weight_decay is None else weight_decay
     mu = w.momentum if momentum is None else momentum
@@ -118,8 +120,13 @@ def run_case(dev, w, *, weight_decay=None, momentum=None, T=None, flat_params=Tr
         e_ptr, m_ptr, a_ptr, ld_state = ctx.state_ptrs()
         assert ld_state >= d and ld_state % 64 == 0
         assert (m_ptr != 0) == (mu != 0)
+        if fused is not None:
+            ctx.set_fused_average(fused)
         if detach is not None:
             ctx.set_detach(w_dev, ldw, detach)
+            # the call itself writes the points of the current state: x_0 in every row
+            torch.cuda.synchronize()
+            assert bit_equal(w_dev.cpu().numpy()[:, :d], ora.detached_points(detach)), "w before the first step"
         for t in range(T):
             g_host = pool[t % w.pool]
             start = (forced or w.forced_start)(t)
@@ -169,6 +176,8 @@ def run_case(dev, w, *, weight_decay=None, momentum=None, T=None, flat_params=Tr
                     exact.setdefault("y", True)
                     exact["y"] &= bit_equal(y_dev.cpu().numpy(), ora.y())
         torch.cuda.synchronize()
+        want = "average=separate" if (split or fused is False) else "average=fused"
+        assert want in ctx.last_kernel(), ctx.last_kernel()
         if mode == "flat":
             reads_x = wd != 0 or detach is not None
             assert ctx.last_path_flat() == (flat_params or not reads_x)
@@ -204,6 +213,16 @@ def run_case(dev, w, *, weight_decay=None, momentum=None, T=None, flat_params=Tr
             assert abs(got[1] - ref["mean_sq"]) <= 1e-10 * scale, (got, ref)
             assert abs(got[2] - ref["lam_star"]) <= 1e-9, (got, ref)
             assert abs(got[3] - ref["dist"]) <= 1e-9 * scale, (got, ref)
+            # the same per worker (same tolerances: float64 sums in another order)
+            pw = torch.full((3 * W,), float("nan"), dtype=torch.float64, device=dev)
+            ctx.diagnostics_workers(pw)
+            torch.cuda.synchronize()
+            pw = pw.cpu().numpy()
+            refw = DefOracle.diagnostics_workers(ora)
+            assert np.abs(pw[:W] - refw["norm_sq"]).max() <= 1e-10 * scale * W, (pw, refw)
+            assert np.abs(pw[W:2 * W] - refw["inner"]).max() <= 1e-10 * scale * W, (pw, refw)
+            assert np.abs(pw[2 * W:] - refw["lam_star"]).max() <= 1e-9, (pw, refw)
+            assert abs(pw[W:2 * W].mean() - got[0]) <= 1e-10 * scale
         if detach is not None:
             # the stand-alone call, with another lambda, on the final state
             w2 = torch.full((W, d + 3), float("nan"), dtype=torch.float32, device=dev)
@@ -302,6 +321,34 @@ def test_hyperparameter_paths(dev, mu, wd, mode):
     assert exact["x"] and exact["e"], exact
 
 
+@pytest.mark.parametrize("mode,flat_params,mu,wd,detach,W", [
+    ("flat", True, 0.9, 1e-4, None, 5),
+    ("flat", True, 0.0, 0.0, None, 1),
+    ("flat", True, 0.9, 0.0, 0.3, 17),
+    ("tensors", False, 0.9, 1e-3, 0.3, 4),
+    ("flat", False, 0.5, 1e-3, None, 33),
+])
+def test_average_in_a_second_launch(dev, mode, flat_params, mu, wd, detach, W):
+    """def_set_fused_average(0): the LDS-staged averaging kernel after the streaming pass
+    instead of the average folded into it; results are the same bits."""
+    base = wl.resnet50_shaped()
+    w = wl.shrunk(base, d=30011, n_tensors=9, W=W, R=7, T=7, pool=3)
+    exact = run_case(dev, w, momentum=mu, weight_decay=wd, mode=mode, flat_params=flat_params,
+                     detach=detach, fused=False, forced=lambda t: {1: w.d - 3, 4: 0}.get(t))
+    assert all(exact.values()), exact
+
+
+@pytest.mark.parametrize("d,W,R", [(300, 3, 1), (1000, 40, 1), (5000, 2, 2), (66000, 9, 3), (257, 1, 257)])
+def test_fused_average_with_large_blocks(dev, d, W, R):
+    """Blocks that cover the whole vector (R = 1: every wave keeps all its elements, every
+    step wraps) or a large part of it, many workers, and a one-element block: the counters
+    that tell the streaming launch when a piece of the block is complete must come out
+    right for every shape and return to zero for the next step."""
+    w = wl.shrunk(wl.tiny(), d=d, n_tensors=3 if d > 300 else 1, W=W, R=R, T=6, pool=3)
+    exact = run_case(dev, w, momentum=0.9, weight_decay=1e-3, forced=lambda t: {2: d - 1, 3: d // 2}.get(t))
+    assert all(exact.values()), exact
+
+
 # --------------------------------------------------------------------------- #
 # Detached evaluation points written in the same pass (Algorithm 1, "detach" line).
 # --------------------------------------------------------------------------- #
@@ -337,6 +384,14 @@ def test_detach_rejects_bad_arguments(dev):
         assert ei.value.status == binding.DEF_EINVAL
     ctx.set_detach(wbuf, 1024, 0.3)
     ctx.set_detach(None)
+    # not between the two halves of a split iteration
+    g = torch.zeros(W, 1024, device=dev)
+    block = ctx.pack(g, 1024)
+    with pytest.raises(binding.DefError) as ei:
+        ctx.set_detach(wbuf, 1024, 0.3)
+    assert ei.value.status == binding.DEF_EINVAL
+    ctx.apply(block, float(W))
+    ctx.set_detach(wbuf, 1024, 0.3)
     ctx.destroy()
 
 
