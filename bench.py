@@ -153,6 +153,10 @@ def main() -> int:
     ap.add_argument("--misaligned", action="store_true",
                     help="offset the gradient buffers by one float (rows 4-byte but not 16-byte "
                          "aligned)")
+    ap.add_argument("--kernel-timing", default="two-pass", choices=["two-pass", "inline"],
+                    help="two-pass: the K timed steps run without per-launch events (value, ms_per_step), "
+                         "then K more steps run with a HIP event pair around every streaming launch "
+                         "(roofline); inline: the event pairs are recorded inside the timed steps")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="N",
                     help="first run N plain device-to-device copies of a 1 GiB tensor (a kernel of "
                          "known traffic, 2^30 bytes read and 2^30 written per launch, against which "
@@ -278,7 +282,8 @@ def main() -> int:
         elapsed = time.perf_counter() - t0
         kernel_ms = None
     else:
-        ctx.profile_begin(args.steps)
+        if args.kernel_timing == "inline":
+            ctx.profile_begin(args.steps)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for _ in range(args.steps):
@@ -286,6 +291,18 @@ def main() -> int:
             t += 1
         torch.cuda.synchronize()
         elapsed = time.perf_counter() - t0
+        if args.kernel_timing == "two-pass":
+            # the same K steps again, each streaming launch between two HIP events on its stream
+            ctx.profile_begin(args.steps)
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+            for _ in range(args.steps):
+                one_step(t)
+                t += 1
+            torch.cuda.synchronize()
+            elapsed_events = time.perf_counter() - t1
+        else:
+            elapsed_events = elapsed
         kernel_ms = ctx.profile_end(args.steps)
     kernel_name = ctx.last_kernel()
     aux = None
@@ -345,7 +362,14 @@ def main() -> int:
                      "min_launch_ms": round(min(kernel_ms), 5) if kernel_ms else None,
                      "median_launch_ms": round(sorted(kernel_ms)[len(kernel_ms) // 2], 5) if kernel_ms else None,
                      "algorithmic_bytes_per_launch": ab["stream_kernel"],
-                     "traffic": MEASURED_TRAFFIC.get((w.name, kernel_name))},
+                     "timed_in": None if not kernel_ms else (
+                         "the timed steps themselves" if args.kernel_timing == "inline" else
+                         f"a second pass of {args.steps} steps right after the timed ones, "
+                         f"{elapsed_events / args.steps * 1e3:.5f} ms per step with the events"),
+                     "traffic": MEASURED_TRAFFIC.get((w.name, kernel_name)),
+                     "traffic_source": "rocprofv3 FETCH_SIZE + WRITE_SIZE of an earlier run of this kernel "
+                                       "on this workload (profiles/), not of this run"
+                                       if (w.name, kernel_name) in MEASURED_TRAFFIC else None},
     }
     if aux is not None:
         out["aux_kernels"] = aux

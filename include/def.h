@@ -226,18 +226,6 @@ int def_diagnostics(def_ctx *ctx, float lambda, double *out);
  */
 int def_diagnostics_workers(def_ctx *ctx, double *out);
 
-/*
- * Where def_step / def_a_step (and their tensor forms) form the cross-worker average
- * (Algorithm 1, all-reduce and update lines).
- *   on != 0 (default)  inside the streaming launch: the wave that stores the last kept
- *                      element of a 256-column piece of the block adds that piece over
- *                      the workers (k = 0..W-1 in order) and updates x there; a step is
- *                      one kernel launch.
- *   on == 0            in a second launch after the streaming pass (LDS-staged rows).
- * Both give bit-identical results.  def_pack / def_apply always use separate launches.
- */
-int def_set_fused_average(def_ctx *ctx, int on);
-
 /* Replace the seed (Sec. 1: the seed all workers share).  t keeps counting. */
 int def_set_seed(def_ctx *ctx, uint64_t seed);
 

@@ -47,7 +47,6 @@ SIGNATURES = {
     "def_detach": (ctypes.c_int, [_vp, _vp, _u64, _f32]),
     "def_diagnostics": (ctypes.c_int, [_vp, _f32, _vp]),
     "def_diagnostics_workers": (ctypes.c_int, [_vp, _vp]),
-    "def_set_fused_average": (ctypes.c_int, [_vp, ctypes.c_int]),
     "def_block_length": (ctypes.c_int, [_vp, ctypes.POINTER(_u64)]),
     "def_set_seed": (ctypes.c_int, [_vp, _u64]),
     "def_set_device_draw": (ctypes.c_int, [_vp, ctypes.c_int]),
@@ -266,9 +265,6 @@ class DefContext:
         _check(self._lib.def_diagnostics_workers(self._h, _ptr(out)), "def_diagnostics_workers")
 
     # -- knobs ----------------------------------------------------------------
-    def set_fused_average(self, on: bool) -> None:
-        _check(self._lib.def_set_fused_average(self._h, 1 if on else 0), "def_set_fused_average")
-
     def set_seed(self, seed: int) -> None:
         _check(self._lib.def_set_seed(self._h, seed), "def_set_seed")
 

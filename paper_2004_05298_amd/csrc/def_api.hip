@@ -105,8 +105,6 @@ struct def_ctx {
     float *e = nullptr, *m = nullptr, *msg = nullptr, *avg = nullptr;
     double *diag = nullptr;   // per-workgroup partial sums of def_diagnostics
     double *diag_workers = nullptr;   // per-workgroup partial sums of def_diagnostics_workers
-    uint32_t *tile_count = nullptr;   // one counter per DEF_AVG_TILE block columns (fused average)
-    bool fused_average = true;        // def_step folds the average + update into the streaming launch
     DefCtl *ctl = nullptr;    // device copy of (t, seed, forced, s) for the device draw
     bool device_draw = false;
     uint64_t ld = 0, ldmsg = 0;
@@ -148,7 +146,6 @@ void free_ctx(def_ctx *c)
     (void)hipFree(c->avg);
     (void)hipFree(c->diag);
     (void)hipFree(c->diag_workers);
-    (void)hipFree(c->tile_count);
     (void)hipFree(c->ctl);
     (void)hipFree(c->d_off);
     (void)hipFree(c->d_tile_tensor);
@@ -164,7 +161,6 @@ DefStepArgs base_args(const def_ctx *c, uint64_t s)
     a.lr = c->lr; a.mu = c->mu; a.wd = c->wd;
     a.e = c->e; a.m = c->m; a.ld = c->ld;
     a.msg = c->msg; a.ldmsg = c->ldmsg; a.avg = c->avg;
-    a.tile_count = nullptr;
     a.x_flat = c->x_flat; a.x_ptrs = c->d_xptrs; a.off = c->d_off; a.L = c->L;
     a.tile_tensor = c->d_tile_tensor;
     a.w = c->w; a.ldw = c->ldw; a.lam = c->lam;
@@ -210,10 +206,9 @@ int run_stream(def_ctx *c, DefStepArgs &a)
 // The sequence of one iteration: streaming pass, average + update, optional y.
 int run_step(def_ctx *c, DefStepArgs &a, float *y_out)
 {
-    if (c->fused_average) a.tile_count = c->tile_count;
     const int rc = run_stream(c, a);
     if (rc != DEF_OK) return rc;
-    if (!a.tile_count) DEF_HIP(def_launch_average_update(a, c->stream));
+    DEF_HIP(def_launch_average_update(a, c->stream));
     if (y_out) DEF_HIP(def_launch_output(a, y_out, c->stream));
     return DEF_OK;
 }
@@ -365,9 +360,6 @@ int def_init(def_ctx **out, const def_config *cfg)
     DEF_INIT_HIP(hipMalloc((void **)&c->diag, def_diag_blocks(c->d) * 2 * sizeof(double)));
     DEF_INIT_HIP(hipMalloc((void **)&c->diag_workers,
                            def_diag_worker_blocks(c->d) * 2 * (size_t)c->W * sizeof(double)));
-    const size_t count_bytes = c->ldmsg / DEF_AVG_TILE * sizeof(uint32_t);
-    DEF_INIT_HIP(hipMalloc((void **)&c->tile_count, count_bytes));
-    DEF_INIT_HIP(hipMemsetAsync(c->tile_count, 0, count_bytes, c->stream));
     DEF_INIT_HIP(hipMalloc((void **)&c->ctl, sizeof(DefCtl)));
     DEF_INIT_HIP(hipMemsetAsync(c->ctl, 0, sizeof(DefCtl), c->stream));
 
@@ -554,13 +546,6 @@ int def_diagnostics_workers(def_ctx *ctx, double *out)
     DEF_ON_DEVICE(ctx);
     DefStepArgs a = base_args(ctx, 0);
     DEF_HIP(def_launch_diagnostics_workers(a, ctx->diag_workers, out, ctx->stream));
-    return DEF_OK;
-}
-
-int def_set_fused_average(def_ctx *ctx, int on)
-{
-    if (!ctx) return DEF_EINVAL;
-    ctx->fused_average = on != 0;
     return DEF_OK;
 }
 

@@ -78,9 +78,6 @@ struct DefStepArgs {
     float *msg;        // [W][ldmsg] compact compressed vectors C(p_k): entry j <-> index (s+j) mod d
     uint64_t ldmsg;    // multiple of DEF_AVG_TILE
     float *avg;        // [B] averaged block
-    // not null: the streaming pass itself averages the kept block and updates x (one counter
-    // per DEF_AVG_TILE block columns, all zero between steps); null: a second kernel does
-    uint32_t *tile_count;
     // parameters x
     float *x_flat;             // flat mode, else nullptr
     float *const *x_ptrs;      // DEVICE table of L tensor pointers (tensor mode), else nullptr

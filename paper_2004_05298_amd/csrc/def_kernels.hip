@@ -128,10 +128,6 @@ __device__ __forceinline__ bool decode_item(uint64_t total, uint64_t tiles, uint
     return true;
 }
 
-// Defined with the averaging kernels below: counts the kept elements a wave has just
-// stored, and averages every tile of the compact block that this wave completed.
-__device__ __forceinline__ void finish_block_tiles(const DefStepArgs &a, uint64_t j0, uint32_t kept);
-
 // ---------------------------------------------------------------------------
 // Streaming pass.  One workgroup = one worker's tile of THREADS*U float4 groups;
 // thread t owns groups t, t+THREADS, ... so that each wave instruction touches
@@ -245,13 +241,9 @@ __global__ __launch_bounds__(THREADS) void def_stream_vec4_kernel(DefStepArgs a,
         }
     }
 
-    uint32_t kept_of[U];                                      // bit c: element c of group u was kept
-    uint64_t j0_of[U];                                        // block position of the group's first element
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         const uint64_t i = i_first + u * STRIDE;
-        kept_of[u] = 0;
-        j0_of[u] = 0;
         if (!interior && i >= a.d) continue;
         v4f p;
 #pragma unroll
@@ -264,7 +256,6 @@ __global__ __launch_bounds__(THREADS) void def_stream_vec4_kernel(DefStepArgs a,
         // position of element i inside the circular block: j = (i - s) mod d
         uint64_t j0 = i >= s ? i - s : i + a.d - s;
         v4f en = p;                                           // off-block: e <- p
-        uint32_t kept = 0;                                    // bit c: element i + c is in the block
         if (!(j0 >= a.B && j0 + 3 < a.d)) {                   // some element may be kept
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
@@ -273,12 +264,9 @@ __global__ __launch_bounds__(THREADS) void def_stream_vec4_kernel(DefStepArgs a,
                 if (i + c < a.d && j < a.B) {
                     msg[j] = p[c];                            // C(p_k), compact
                     en[c] = 0.0f;                             // p - C(p) = +0 inside the block
-                    kept |= 1u << c;
                 }
             }
         }
-        kept_of[u] = kept;
-        j0_of[u] = j0;
         if constexpr (HAS_MU) store4<NT_ST>(m + i, mv[u]);
         store4<NT_ST>(e + i, en);
         if constexpr (HAS_DT) {
@@ -299,12 +287,6 @@ __global__ __launch_bounds__(THREADS) void def_stream_vec4_kernel(DefStepArgs a,
                     if (i + c < a.d) w[i + c] = wv[c];
             }
         }
-    }
-    if (a.tile_count) {
-        // all lanes of the wave are here again (those beyond d hold no element: kept == 0)
-        static_assert(THREADS == 64, "the fused average is written for one-wave workgroups");
-#pragma unroll
-        for (int u = 0; u < U; ++u) finish_block_tiles(a, j0_of[u], kept_of[u]);
     }
 }
 
@@ -366,79 +348,6 @@ __device__ __forceinline__ void apply_block_entry(const DefStepArgs &a, uint64_t
         const float scaled = a.lam * 0.0f;
         const float wv = x_new - scaled;
         for (uint32_t k = 0; k < a.W; ++k) a.w[(uint64_t)k * a.ldw + i] = wv;
-    }
-}
-
-// ---------------------------------------------------------------------------
-// The same average and update, folded into the streaming launch (no second kernel, no
-// gap between two launches).  Every wave of the streaming pass that kept elements adds,
-// per tile of DEF_AVG_TILE block columns it touched, the number of elements it stored to
-// that tile's counter in device memory; a tile is complete when its counter reaches
-// W * (columns of the tile), and the wave whose addition completes it sums the W staged
-// rows of that tile in worker order from +0 (the same sum as the kernel above), updates
-// x there and leaves the counter at zero for the next step.  Nobody waits for anybody:
-// every wave adds and leaves, so the grid always drains.  Release/acquire fences of
-// device scope around the counter make the other waves' stores visible (they may have
-// run on another XCD, whose L2 is a different one).
-// Who reads x[i] for an index inside the block (weight decay, detached points) is a wave
-// that also keeps element i, so it has finished its loads before it adds to the counter,
-// hence before x[i] changes.
-// ---------------------------------------------------------------------------
-__device__ __forceinline__ void average_block_tile(const DefStepArgs &a, uint32_t tile)
-{
-    const uint32_t lane = threadIdx.x & 63u;
-    const uint64_t j = (uint64_t)tile * DEF_AVG_TILE + lane * 4;
-    v4f acc = (v4f)(0.0f);
-    for (uint32_t k = 0; k < a.W; ++k)
-        acc = acc + load4<false>(a.msg + (uint64_t)k * a.ldmsg + j);      // rows padded to the tile
-    const v4f cbar = acc / (float)a.W;                                      // (1/W) sum_k C(p_k)
-#pragma unroll
-    for (int c = 0; c < 4; ++c)
-        if (j + c < a.B) apply_block_entry(a, j + c, cbar[c]);
-}
-
-__device__ __forceinline__ void finish_block_tiles(const DefStepArgs &a, uint64_t j0, uint32_t kept)
-{
-    if (__ballot(kept != 0) == 0) return;                   // the wave kept nothing (nearly all waves)
-    __threadfence();                                        // release: this wave's msg stores first
-    const uint32_t lane = threadIdx.x & 63u;
-    uint32_t tile_of[4];
-#pragma unroll
-    for (int c = 0; c < 4; ++c) {
-        uint64_t j = j0 + c;
-        if (j >= a.d) j -= a.d;
-        tile_of[c] = (uint32_t)(j / DEF_AVG_TILE);
-    }
-    // the wave's kept elements lie in at most a few tiles; take them one tile at a time
-    for (;;) {
-        const uint64_t waiting = __ballot(kept != 0);
-        if (waiting == 0) break;
-        uint32_t mine = 0;
-#pragma unroll
-        for (int c = 3; c >= 0; --c)
-            if (kept >> c & 1u) mine = tile_of[c];          // tile of this lane's first waiting element
-        const uint32_t tile = __shfl(mine, __ffsll((unsigned long long)waiting) - 1, 64);
-        uint32_t n = 0;
-#pragma unroll
-        for (int c = 0; c < 4; ++c)
-            if ((kept >> c & 1u) && tile_of[c] == tile) {
-                ++n;
-                kept &= ~(1u << c);
-            }
-#pragma unroll
-        for (int off = 32; off > 0; off >>= 1) n += __shfl_xor(n, off, 64);      // wave total
-        uint32_t before = 0;
-        if (lane == 0)
-            before = __hip_atomic_fetch_add(a.tile_count + tile, n, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        before = __shfl(before, 0, 64);
-        const uint64_t first_col = (uint64_t)tile * DEF_AVG_TILE;
-        const uint64_t cols = a.B - first_col < DEF_AVG_TILE ? a.B - first_col : DEF_AVG_TILE;
-        if ((uint64_t)before + n == cols * a.W) {           // this wave completed the tile
-            __threadfence();                                // acquire: the other waves' msg stores
-            if (lane == 0)
-                __hip_atomic_store(a.tile_count + tile, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            average_block_tile(a, tile);
-        }
     }
 }
 
@@ -765,10 +674,9 @@ void def_describe_stream_kernel(const DefStepArgs &a, char *out, size_t cap)
     if (reads_x) std::snprintf(order, sizeof order, "blocked:%u", DEF_SUPER_TILES);
     else std::snprintf(order, sizeof order, "linear");
     std::snprintf(out, cap,
-                  "def_stream_vec4_kernel<mu=%d,wd=%d,detach=%d,tables=%d,threads=%u,quads=%u,nt=%d,order=%s,lds=%u,"
-                  "average=%s>",
+                  "def_stream_vec4_kernel<mu=%d,wd=%d,detach=%d,tables=%d,threads=%u,quads=%u,nt=%d,order=%s,lds=%u>",
                   mu, wd, dt, tables, DEF_VEC_THREADS, DEF_VEC_QUADS, (int)streams_non_temporal(a), order,
-                  def_stream_lds_reserve(mu, dt, streams_non_temporal(a)), a.tile_count ? "fused" : "separate");
+                  def_stream_lds_reserve(mu, dt, streams_non_temporal(a)));
 }
 
 // Picks the instantiation for (momentum, weight decay, detached points).  Whenever x

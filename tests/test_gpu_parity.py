@@ -54,12 +54,10 @@ def fetch_avg(ctx):
 def run_case(dev, w, *, weight_decay=None, momentum=None, T=None, flat_params=True,
              mode="flat", misalign=0, ld=None, oracle="np", check_every_step=True,
              with_y=True, special=None, variant=None, forced=None, detach=None, ldw=None,
-             split=False, fused=None):
+             split=False):
     """Run T steps on both sides and compare.  mode: "flat" (one gradient buffer
     [W][ld]) or "tensors" (one allocation per worker and tensor).  split: every
-    iteration is def_pack followed by def_apply of the returned sum with divisor W.
-    fused: False forms the cross-worker average in a second launch instead of inside
-    the streaming launch (the library's default, None here)."""
+    iteration is def_pack followed by def_apply of the returned sum with divisor W."""
     binding = _binding()
     wd = w.weight_decay if weight_decay is None else weight_decay
     mu = w.momentum if momentum is None else momentum
@@ -120,8 +118,6 @@ def run_case(dev, w, *, weight_decay=None, momentum=None, T=None, flat_params=Tr
         e_ptr, m_ptr, a_ptr, ld_state = ctx.state_ptrs()
         assert ld_state >= d and ld_state % 64 == 0
         assert (m_ptr != 0) == (mu != 0)
-        if fused is not None:
-            ctx.set_fused_average(fused)
         if detach is not None:
             ctx.set_detach(w_dev, ldw, detach)
             # the call itself writes the points of the current state: x_0 in every row
@@ -176,8 +172,6 @@ def run_case(dev, w, *, weight_decay=None, momentum=None, T=None, flat_params=Tr
                     exact.setdefault("y", True)
                     exact["y"] &= bit_equal(y_dev.cpu().numpy(), ora.y())
         torch.cuda.synchronize()
-        want = "average=separate" if (split or fused is False) else "average=fused"
-        assert want in ctx.last_kernel(), ctx.last_kernel()
         if mode == "flat":
             reads_x = wd != 0 or detach is not None
             assert ctx.last_path_flat() == (flat_params or not reads_x)
@@ -321,29 +315,11 @@ def test_hyperparameter_paths(dev, mu, wd, mode):
     assert exact["x"] and exact["e"], exact
 
 
-@pytest.mark.parametrize("mode,flat_params,mu,wd,detach,W", [
-    ("flat", True, 0.9, 1e-4, None, 5),
-    ("flat", True, 0.0, 0.0, None, 1),
-    ("flat", True, 0.9, 0.0, 0.3, 17),
-    ("tensors", False, 0.9, 1e-3, 0.3, 4),
-    ("flat", False, 0.5, 1e-3, None, 33),
-])
-def test_average_in_a_second_launch(dev, mode, flat_params, mu, wd, detach, W):
-    """def_set_fused_average(0): the LDS-staged averaging kernel after the streaming pass
-    instead of the average folded into it; results are the same bits."""
-    base = wl.resnet50_shaped()
-    w = wl.shrunk(base, d=30011, n_tensors=9, W=W, R=7, T=7, pool=3)
-    exact = run_case(dev, w, momentum=mu, weight_decay=wd, mode=mode, flat_params=flat_params,
-                     detach=detach, fused=False, forced=lambda t: {1: w.d - 3, 4: 0}.get(t))
-    assert all(exact.values()), exact
-
-
 @pytest.mark.parametrize("d,W,R", [(300, 3, 1), (1000, 40, 1), (5000, 2, 2), (66000, 9, 3), (257, 1, 257)])
-def test_fused_average_with_large_blocks(dev, d, W, R):
+def test_large_blocks_and_many_workers(dev, d, W, R):
     """Blocks that cover the whole vector (R = 1: every wave keeps all its elements, every
-    step wraps) or a large part of it, many workers, and a one-element block: the counters
-    that tell the streaming launch when a piece of the block is complete must come out
-    right for every shape and return to zero for the next step."""
+    step wraps) or a large part of it, more workers than the averaging kernel stages at a
+    time, and a one-element block."""
     w = wl.shrunk(wl.tiny(), d=d, n_tensors=3 if d > 300 else 1, W=W, R=R, T=6, pool=3)
     exact = run_case(dev, w, momentum=0.9, weight_decay=1e-3, forced=lambda t: {2: d - 1, 3: d // 2}.get(t))
     assert all(exact.values()), exact
