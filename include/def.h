@@ -51,7 +51,8 @@ typedef enum def_status {
     DEF_OK = 0,
     DEF_EINVAL = -1,   /* bad argument: NULL pointer, bad shape, bad offset table, ld < d, ... */
     DEF_ENOMEM = -2,   /* device or host allocation failed                                      */
-    DEF_EHIP = -3      /* a HIP runtime call failed; def_last_hip_error() has its code          */
+    DEF_EHIP = -3,     /* a HIP runtime call failed; def_last_hip_error() has its code          */
+    DEF_ELIMIT = -4    /* the problem exceeds a fixed limit of the entry point called           */
 } def_status;
 
 typedef struct def_ctx def_ctx; /* opaque, owned by the library */
@@ -213,6 +214,30 @@ int def_detach(def_ctx *ctx, float *w_out, uint64_t ldw, float lambda);
  * from run to run (no atomics).  DEF_EINVAL for lambda outside [0, 1].
  */
 int def_diagnostics(def_ctx *ctx, float lambda, double *out);
+
+/*
+ * def_diagnostics for callers that cannot allocate device memory and have no context:
+ * code running under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  It computes the same four numbers from error memories the CALLER holds
+ * (a checkpoint it restored itself, or the views of def_state_ptrs) and allocates
+ * nothing, not even at its first call: the per-workgroup partial sums live in a
+ * fixed 4 MiB array inside the library's device image, one copy per GPU, kept until
+ * the process ends.
+ *   e       DEVICE, read-only: worker k's error memory at e + k*ld, d floats used;
+ *           16-byte aligned, ld >= d and a multiple of 4.  Columns d..ld-1 are not read.
+ *   d, W    as in def_config; d <= DEF_STATIC_MAX_D, else DEF_ELIMIT (nothing is run).
+ *   lambda  in [0, 1].
+ *   out     DEVICE, 4 doubles as def_diagnostics writes them, 8-byte aligned.
+ *   stream  hipStream_t of the GPU that is current in the calling thread (NULL = the
+ *           null stream); only two kernel launches are enqueued, no memset, no copy.
+ * Every call on a GPU uses that GPU's one array (fully overwritten as far as it is
+ * read, so nothing needs clearing): calls that overlap in time on one GPU, on different
+ * streams, race with each other; calls on one stream, or on different GPUs, do not.
+ * Results are bit-identical to def_diagnostics on the same error memories.
+ */
+#define DEF_STATIC_MAX_D ((uint64_t)268435456)   /* 2^19 doubles / 2 per 1024 columns */
+int def_diagnostics_static(const float *e, uint64_t ld, uint64_t d, uint32_t W, float lambda, double *out,
+                           void *stream);
 
 /*
  * The same per worker (Sec. 3.2, item (1); Appendix A, first display): for

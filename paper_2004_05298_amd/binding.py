@@ -13,7 +13,8 @@ from typing import List, Optional, Sequence
 
 from . import build as _build
 
-DEF_OK, DEF_EINVAL, DEF_ENOMEM, DEF_EHIP = 0, -1, -2, -3
+DEF_OK, DEF_EINVAL, DEF_ENOMEM, DEF_EHIP, DEF_ELIMIT = 0, -1, -2, -3, -4
+DEF_STATIC_MAX_D = 268435456
 
 _u64, _u32, _i64, _f32 = ctypes.c_uint64, ctypes.c_uint32, ctypes.c_int64, ctypes.c_float
 _vp = ctypes.c_void_p
@@ -46,6 +47,7 @@ SIGNATURES = {
     "def_set_detach": (ctypes.c_int, [_vp, _vp, _u64, _f32]),
     "def_detach": (ctypes.c_int, [_vp, _vp, _u64, _f32]),
     "def_diagnostics": (ctypes.c_int, [_vp, _f32, _vp]),
+    "def_diagnostics_static": (ctypes.c_int, [_vp, _u64, _u64, _u32, _f32, _vp, _vp]),
     "def_diagnostics_workers": (ctypes.c_int, [_vp, _vp]),
     "def_block_length": (ctypes.c_int, [_vp, ctypes.POINTER(_u64)]),
     "def_set_seed": (ctypes.c_int, [_vp, _u64]),
@@ -111,6 +113,12 @@ def block_start(seed: int, t: int, d: int) -> int:
     out = _u64()
     _check(load_library().def_block_start(seed, t, d, ctypes.byref(out)), "def_block_start")
     return out.value
+
+
+def diagnostics_static(e, ld: int, d: int, W: int, lam: float, out, stream: int = 0) -> None:
+    """def_diagnostics_static: e is a device tensor (or address) [W][ld], out 4 float64 on the device."""
+    _check(load_library().def_diagnostics_static(_ptr(e), ld, d, W, lam, _ptr(out), stream),
+           "def_diagnostics_static")
 
 
 def _ptr(t) -> int:

@@ -361,6 +361,12 @@ int def_init(def_ctx **out, const def_config *cfg)
     DEF_INIT_HIP(hipMalloc((void **)&c->diag_workers,
                            def_diag_worker_blocks(c->d) * 2 * (size_t)c->W * sizeof(double)));
     DEF_INIT_HIP(hipMalloc((void **)&c->ctl, sizeof(DefCtl)));
+    {
+        // look the static scratch array of def_diagnostics_static up now, on this GPU, so that
+        // a later call of it (possibly while the stream is being captured) finds it resolved
+        double *unused = nullptr;
+        DEF_INIT_HIP(def_static_scratch_address(&unused));
+    }
     DEF_INIT_HIP(hipMemsetAsync(c->ctl, 0, sizeof(DefCtl), c->stream));
 
     // (the large device buffers come first so that a problem that does not fit fails
@@ -540,6 +546,24 @@ int def_diagnostics(def_ctx *ctx, float lambda, double *out)
     return DEF_OK;
 }
 
+int def_diagnostics_static(const float *e, uint64_t ld, uint64_t d, uint32_t W, float lambda, double *out,
+                           void *stream)
+{
+    if (!e || !out || d == 0 || W == 0 || ld < d || ld % 4 != 0 || (uintptr_t)e % 16 != 0 ||
+        (uintptr_t)out % 8 != 0 || !(lambda >= 0.0f && lambda <= 1.0f))
+        return DEF_EINVAL;
+    const uint64_t blocks = def_diag_blocks(d);
+    if (blocks * 2 > DEF_STATIC_SCRATCH_DOUBLES) return DEF_ELIMIT;   // d > DEF_STATIC_MAX_D
+    double *scratch = nullptr;
+    DEF_HIP(def_static_scratch_address(&scratch));
+    DefStepArgs a{};
+    a.d = d; a.W = W; a.ld = ld;
+    a.e = const_cast<float *>(e);                 // the statistics kernels only read it
+    // every partial sum the second kernel reads is written by the first: nothing to clear
+    DEF_HIP(def_launch_diagnostics(a, lambda, scratch, out, (hipStream_t)stream));
+    return DEF_OK;
+}
+
 int def_diagnostics_workers(def_ctx *ctx, double *out)
 {
     if (!ctx || !out || (uintptr_t)out % 8 != 0) return DEF_EINVAL;
@@ -705,6 +729,7 @@ const char *def_strerror(int status)
     case DEF_EINVAL: return "invalid argument";
     case DEF_ENOMEM: return "out of memory";
     case DEF_EHIP: return "HIP runtime error (see def_last_hip_error)";
+    case DEF_ELIMIT: return "problem larger than the fixed limit of this entry point";
     default: return "unknown status";
     }
 }

@@ -120,6 +120,10 @@ hipError_t def_launch_output(const DefStepArgs &a, float *y, hipStream_t st);
 uint64_t def_diag_blocks(uint64_t d);
 hipError_t def_launch_diagnostics(const DefStepArgs &a, float lambda, double *partials, double *out,
                                   hipStream_t st);
+// Device address, on the GPU that is current, of the library's static scratch array of
+// DEF_STATIC_SCRATCH_DOUBLES doubles (looked up once per GPU; no allocation).
+constexpr uint64_t DEF_STATIC_SCRATCH_DOUBLES = 1ull << 19;      // 4 MiB
+hipError_t def_static_scratch_address(double **ptr);
 // w_k = x - lambda*e_k for the current state (a.w, a.ldw, a.lam).
 hipError_t def_launch_detach(const DefStepArgs &a, hipStream_t st);
 // Per-worker statistics ||e_k||^2, <e_t, e_k> and their ratio lambda*(k,t), as 3*W doubles in out.

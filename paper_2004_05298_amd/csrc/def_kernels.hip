@@ -26,6 +26,7 @@
 #include "def_internal.h"
 
 #include <cstdio>
+#include <mutex>
 
 #pragma clang fp contract(off)
 
@@ -479,9 +480,18 @@ __global__ __launch_bounds__(DEF_THREADS) void def_diag_partial_kernel(DefStepAr
     double s1 = 0.0, s2 = 0.0;
     if (i < a.d) {
         double acc[4] = {0.0, 0.0, 0.0, 0.0};
+        const bool whole = i + 4 <= a.d;     // the last group of a row may be cut by d
 #pragma unroll 16
         for (uint32_t k = 0; k < a.W; ++k) {
-            const v4f ev = load4<true>(a.e + (uint64_t)k * a.ld + i);   // padding columns hold zeros
+            const float *row = a.e + (uint64_t)k * a.ld + i;
+            v4f ev = (v4f)(0.0f);
+            if (whole) {
+                ev = load4<true>(row);
+            } else {
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+                    if (i + c < a.d) ev[c] = row[c];
+            }
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
                 const double v = (double)ev[c];
@@ -808,6 +818,39 @@ hipError_t def_launch_diagnostics_workers(const DefStepArgs &a, double *partials
     }
     def_diag_workers_final_kernel<<<dim3(1), dim3(DEF_THREADS), 0, st>>>(partials, rows, a.W, out);
     return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// Device memory that belongs to the library image itself: the per-workgroup partial
+// sums of def_diagnostics_static, so that this one entry point needs no allocation.
+// Every GPU holds its own copy at its own address; the name below is a host-side
+// handle and must never be passed to a kernel: the device address is looked up once
+// per GPU with hipGetSymbolAddress and kept.
+// ---------------------------------------------------------------------------
+static __device__ __align__(256) double def_static_scratch[DEF_STATIC_SCRATCH_DOUBLES];
+
+namespace {
+constexpr int MAX_DEVICES = 64;
+double *g_static_scratch_ptr[MAX_DEVICES];   // device address of def_static_scratch on each GPU
+std::mutex g_static_scratch_mutex;
+}  // namespace
+
+hipError_t def_static_scratch_address(double **ptr)
+{
+    int device = -1;
+    hipError_t err = hipGetDevice(&device);
+    if (err != hipSuccess) return err;
+    if (device < 0 || device >= MAX_DEVICES) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_static_scratch_mutex);
+    if (!g_static_scratch_ptr[device]) {
+        void *found = nullptr;
+        err = hipGetSymbolAddress(&found, HIP_SYMBOL(def_static_scratch));   // for the current GPU
+        if (err != hipSuccess) return err;
+        if (!found) return hipErrorInvalidSymbol;
+        g_static_scratch_ptr[device] = static_cast<double *>(found);
+    }
+    *ptr = g_static_scratch_ptr[device];
+    return hipSuccess;
 }
 
 hipError_t def_launch_detach(const DefStepArgs &a, hipStream_t st)

@@ -137,3 +137,22 @@ def test_binding_checks_table_lengths_before_calling_the_library(lib):
     with pytest.raises(ValueError, match="5 gradient tensors given, W\\*n_tensors = 6"):
         ctx._gtable([4096] * 5)
     assert len(ctx._gtable([4096] * 6)) == 6
+
+
+def test_static_entry_point_checks_sizes_before_touching_the_gpu(lib):
+    """def_diagnostics_static validates its arguments, and refuses problems beyond the
+    size its fixed scratch array covers, before any HIP call."""
+    big = binding.DEF_STATIC_MAX_D
+    call = lib.def_diagnostics_static
+    assert call(4096, big + 4, big + 1, 1, 0.3, 8192, None) == binding.DEF_ELIMIT
+    assert lib.def_strerror(binding.DEF_ELIMIT) == b"problem larger than the fixed limit of this entry point"
+    for args in [(None, 128, 100, 2, 0.3, 8192, None),        # no error memories
+                 (4096, 128, 100, 2, 0.3, None, None),         # no output
+                 (4096, 128, 0, 2, 0.3, 8192, None),           # d = 0
+                 (4096, 128, 100, 0, 0.3, 8192, None),         # W = 0
+                 (4096, 96, 100, 2, 0.3, 8192, None),          # ld < d
+                 (4096, 102, 100, 2, 0.3, 8192, None),         # ld not a multiple of 4
+                 (4100, 128, 100, 2, 0.3, 8192, None),         # rows not 16-byte aligned
+                 (4096, 128, 100, 2, 0.3, 8196, None),         # output not 8-byte aligned
+                 (4096, 128, 100, 2, 1.5, 8192, None)]:        # lambda outside [0, 1]
+        assert call(*args) == binding.DEF_EINVAL, args
