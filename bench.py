@@ -36,7 +36,7 @@ HBM_PEAK_GBS = 8000.0   # MI355X HBM3E peak, GB/s
 # counters are taken again.
 MEASURED_TRAFFIC = {
     ("resnet50_shaped",
-     "def_stream_vec4_kernel<mu=1,wd=1,detach=0,tables=0,threads=64,quads=1,nt=1,order=blocked:16384,lds=10240>"): 8306293271,
+     "def_stream_vec4_kernel<mu=1,wd=1,detach=0,tables=0,threads=64,quads=1,nt=1,order=blocked:16384,sweep=alternating,lds=10240>"): None,
 }
 
 
@@ -105,6 +105,44 @@ def cpu_baseline(w, ld, budget_s=15.0):
     }
 
 
+def run_probes(torch, binding, stream, src, n, reps=20):
+    """What plain streaming kernels of known traffic sustain on this GPU, right after the
+    timed steps: pure read, pure write, copy and in-place update over a buffer of the size
+    of one state buffer, the best of seven launch shapes each (among them the streaming
+    pass's own, with and without its residency cap).  Context for the roofline fraction,
+    not part of the step."""
+    n = min(n, 1 << 29) // 256 * 256
+    if src is None:
+        src = torch.zeros(n, dtype=torch.float32, device="cuda")
+    dst = torch.empty(n, dtype=torch.float32, device="cuda")
+    dst.zero_()
+    kinds = [("read", binding.PROBE_READ, 4 * n), ("write", binding.PROBE_WRITE, 4 * n),
+             ("copy", binding.PROBE_COPY, 8 * n), ("update_in_place", binding.PROBE_UPDATE, 8 * n)]
+    out = {"bytes_per_buffer": 4 * n, "launches_each": reps}
+    shapes = [(64, 1, 0), (64, 1, 10240), (64, 2, 0), (64, 4, 0), (256, 1, 0), (256, 2, 0), (256, 4, 0)]
+    for name, kind, nbytes in kinds:
+        best, every = None, {}
+        for threads, quads, lds in shapes:
+            def launch():
+                binding.probe_stream(kind, src, dst, n, 1.0, threads, quads, lds, stream)
+            launch()
+            launch()
+            torch.cuda.synchronize()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            for _ in range(reps):
+                launch()
+            b.record()
+            torch.cuda.synchronize()
+            gbs = nbytes / (a.elapsed_time(b) / reps) / 1e6
+            every[f"{threads}x{quads}/{lds}"] = round(gbs)
+            if best is None or gbs > best[0]:
+                best = (gbs, f"{threads} threads x {quads} float4, lds {lds}")
+        out[name] = {"GB/s": round(best[0], 1), "frac_of_peak": round(best[0] / HBM_PEAK_GBS, 4),
+                     "best_shape": best[1], "all_shapes_GB/s": every}
+    return out
+
+
 def cpu_model() -> str:
     try:
         with open("/proc/cpuinfo") as f:
@@ -131,6 +169,11 @@ def main() -> int:
     ap.add_argument("--workers", type=int, default=None, metavar="W",
                     help="override the workload's number of workers on this GPU (W = 1 is one GPU's "
                          "share when the workers are spread one per GPU)")
+    ap.add_argument("--momentum", type=float, default=None, metavar="MU",
+                    help="override the workload's momentum (0 drops the momentum buffer: three streams "
+                         "per worker and index instead of five)")
+    ap.add_argument("--weight-decay", type=float, default=None, metavar="WD",
+                    help="override the workload's weight decay (0: the pass does not read x)")
     ap.add_argument("--split", action="store_true",
                     help="run every iteration as def_pack + def_apply (the two halves between which "
                          "a multi-GPU deployment would all-reduce the kept block), applying the "
@@ -158,9 +201,12 @@ def main() -> int:
                          "then K more steps run with a HIP event pair around every streaming launch "
                          "(roofline); inline: the event pairs are recorded inside the timed steps")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="N",
-                    help="first run N plain device-to-device copies of a 1 GiB tensor (a kernel of "
-                         "known traffic, 2^30 bytes read and 2^30 written per launch, against which "
-                         "hardware counters are scaled); not part of the timed region")
+                    help="first run N launches of the library's plain copy probe on a 1 GiB buffer (a "
+                         "kernel of known traffic, 2^30 bytes read and 2^30 written per launch, against "
+                         "which hardware counters are scaled); not part of the timed region")
+    ap.add_argument("--no-probes", action="store_true",
+                    help="skip the plain read / write / copy / in-place probes (include/def_probe.h) that "
+                         "are timed after the steps to show what this GPU sustains in the same run")
     args = ap.parse_args()
 
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -183,14 +229,18 @@ def main() -> int:
         src = torch.zeros(1 << 28, dtype=torch.float32, device="cuda")
         dst = torch.empty_like(src)
         for _ in range(args.copy_calibration):
-            dst.copy_(src)
+            binding.probe_stream(binding.PROBE_COPY, src, dst, 1 << 28, 1.0, 64, 1, 0,
+                                 torch.cuda.current_stream().cuda_stream)
         torch.cuda.synchronize()
         del src, dst
 
     w = wl.by_name(args.workload)
     if args.workers is not None:
-        import dataclasses
-        w = dataclasses.replace(w, W=args.workers)
+        w = w.replace(W=args.workers)
+    if args.momentum is not None:
+        w = w.replace(momentum=args.momentum)
+    if args.weight_decay is not None:
+        w = w.replace(weight_decay=args.weight_decay)
     variant = args.variant or ("def_a" if w.variant == "def_a" else "def")
     if args.with_y and variant == "def_a":
         print("bench.py: --with-y asks for DEF's output; DEF-A's output is x itself", file=sys.stderr)
@@ -310,6 +360,7 @@ def main() -> int:
         y = torch.empty(w.d, dtype=torch.float32, device="cuda")
         wbuf = w_out if w_out is not None else torch.empty((w.W, ld), dtype=torch.float32, device="cuda")
         stats = torch.zeros(4, dtype=torch.float64, device="cuda")
+        stats_w = torch.zeros(3 * w.W, dtype=torch.float64, device="cuda")
         state = 4 * w.W * w.d
 
         def timed(fn, nbytes, reps=20):
@@ -328,8 +379,12 @@ def main() -> int:
             "def_output": timed(lambda: ctx.output(y), state + 8 * w.d),
             "def_detach": timed(lambda: ctx.detach(wbuf, ld, 0.3), 2 * state + 4 * w.d),
             "def_diagnostics": timed(lambda: ctx.diagnostics(0.3, stats), state),
+            "def_diagnostics_workers": timed(lambda: ctx.diagnostics_workers(stats_w), state * -(-w.W // 16)),
         }
     ctx.destroy()
+    probes = None
+    if not args.no_probes and not args.graph:
+        probes = run_probes(torch, binding, stream, pool[0] if pool is not None else None, w.W * ld)
 
     ab = algorithmic_bytes(w, y_out=args.with_y, detach=args.detach is not None)
     per_step = elapsed / args.steps
@@ -369,10 +424,12 @@ def main() -> int:
                      "traffic": MEASURED_TRAFFIC.get((w.name, kernel_name)),
                      "traffic_source": "rocprofv3 FETCH_SIZE + WRITE_SIZE of an earlier run of this kernel "
                                        "on this workload (profiles/), not of this run"
-                                       if (w.name, kernel_name) in MEASURED_TRAFFIC else None},
+                                       if MEASURED_TRAFFIC.get((w.name, kernel_name)) else None},
     }
     if aux is not None:
         out["aux_kernels"] = aux
+    if probes is not None:
+        out["probes"] = probes
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, ld, args.cpu_budget)
         for part in (out["cpu_baseline"], out["cpu_baseline"]["one_thread"]):

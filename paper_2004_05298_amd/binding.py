@@ -65,6 +65,7 @@ SIGNATURES = {
     "def_last_kernel": (ctypes.c_char_p, [_vp]),
     "def_profile_begin": (ctypes.c_int, [_vp, _u32]),
     "def_profile_end": (ctypes.c_int, [_vp, ctypes.POINTER(_f32), _u32, ctypes.POINTER(_u32)]),
+    "def_probe_stream": (ctypes.c_int, [ctypes.c_int, _vp, _vp, _u64, _f32, _u32, _u32, _u32, _vp]),
     "def_strerror": (ctypes.c_char_p, [ctypes.c_int]),
     "def_last_hip_error": (ctypes.c_int, []),
 }
@@ -119,6 +120,16 @@ def diagnostics_static(e, ld: int, d: int, W: int, lam: float, out, stream: int 
     """def_diagnostics_static: e is a device tensor (or address) [W][ld], out 4 float64 on the device."""
     _check(load_library().def_diagnostics_static(_ptr(e), ld, d, W, lam, _ptr(out), stream),
            "def_diagnostics_static")
+
+
+PROBE_READ, PROBE_WRITE, PROBE_COPY, PROBE_UPDATE = 0, 1, 2, 3
+
+
+def probe_stream(kind: int, src, dst, n: int, value: float = 1.0, threads: int = 64, quads: int = 1,
+                 lds_reserve: int = 10240, stream: int = 0) -> None:
+    """def_probe_stream (include/def_probe.h): one streaming launch of known traffic."""
+    _check(load_library().def_probe_stream(kind, _ptr(src), _ptr(dst), n, value, threads, quads,
+                                           lds_reserve, stream), "def_probe_stream")
 
 
 def _ptr(t) -> int:

@@ -10,8 +10,10 @@ _ROOT = os.path.dirname(_PKG)
 _CSRC = os.path.join(_PKG, "csrc")
 _LIB = os.path.join(_PKG, "libdef_hip.so")
 
-SOURCES = [os.path.join(_CSRC, "def_api.hip"), os.path.join(_CSRC, "def_kernels.hip")]
-HEADERS = [os.path.join(_CSRC, "def_internal.h"), os.path.join(_ROOT, "include", "def.h")]
+SOURCES = [os.path.join(_CSRC, "def_api.hip"), os.path.join(_CSRC, "def_kernels.hip"),
+           os.path.join(_CSRC, "def_probe.hip")]
+HEADERS = [os.path.join(_CSRC, "def_internal.h"), os.path.join(_ROOT, "include", "def.h"),
+           os.path.join(_ROOT, "include", "def_probe.h")]
 
 # -ffp-contract=off: every multiply and add rounds separately (results must not
 #   depend on whether the compiler fuses them).

@@ -158,6 +158,7 @@ DefStepArgs base_args(const def_ctx *c, uint64_t s)
 {
     DefStepArgs a{};
     a.d = c->d; a.B = c->B; a.s = s; a.W = c->W;
+    a.backwards = (uint32_t)(c->t & 1u);
     a.lr = c->lr; a.mu = c->mu; a.wd = c->wd;
     a.e = c->e; a.m = c->m; a.ld = c->ld;
     a.msg = c->msg; a.ldmsg = c->ldmsg; a.avg = c->avg;

@@ -60,6 +60,7 @@ struct DefCtl {
     uint64_t seed;    // shared seed
     int64_t forced;   // >= 0: start to use for the next step only
     uint64_t s;       // start drawn for the step in flight
+    uint32_t backwards;   // sweep direction of the step in flight (t odd)
 };
 
 // Everything one step needs on the device.
@@ -68,6 +69,7 @@ struct DefStepArgs {
     uint64_t d;        // parameters
     uint64_t B;        // block length
     uint64_t s;        // block start s_t (host draw)
+    uint32_t backwards; // host draw: the streaming pass sweeps its work items in reverse (odd t)
     const DefCtl *ctl; // not null: the start is ctl->s, drawn on the device by def_launch_draw
     uint32_t W;        // workers
     float lr, mu, wd;  // eta, mu, weight decay

@@ -93,6 +93,12 @@ __device__ __forceinline__ uint64_t block_start_of(const DefStepArgs &a)
     return a.ctl ? a.ctl->s : a.s;
 }
 
+// Direction of the step's sweep over the work items: every other step runs backwards.
+__device__ __forceinline__ bool sweep_backwards(const DefStepArgs &a)
+{
+    return (a.ctl ? a.ctl->backwards : a.backwards) != 0;
+}
+
 // Workgroup ids are dealt round-robin to the 8 XCDs.  Work items (one worker's
 // piece of one column tile) are numbered 0..tiles*W-1 and workgroup b takes item b;
 // MAP chooses what item b is:
@@ -110,10 +116,12 @@ enum { MAP_LINEAR_T = 2, MAP_BLOCKED = 4 };
 
 template <int MAP>
 __device__ __forceinline__ bool decode_item(uint64_t total, uint64_t tiles, uint32_t W, uint32_t super,
-                                            uint32_t &k, uint64_t &tile)
+                                            uint32_t &k, uint64_t &tile, bool backwards = false)
 {
-    const uint64_t item = blockIdx.x;
-    if (item >= total) return false;
+    if (blockIdx.x >= total) return false;
+    // backwards: the same items in the opposite order, so that a pass starts where the
+    // previous one ended and finds the end of that pass still in the caches
+    const uint64_t item = backwards ? total - 1 - blockIdx.x : (uint64_t)blockIdx.x;
     if constexpr (MAP == MAP_LINEAR_T) {
         tile = item % tiles;
         k = (uint32_t)(item / tiles);
@@ -150,7 +158,7 @@ __global__ __launch_bounds__(THREADS) void def_stream_vec4_kernel(DefStepArgs a,
     constexpr bool HAS_X = HAS_WD || HAS_DT;             // x is read for weight decay and for w
     uint32_t k;
     uint64_t tile;
-    if (!decode_item<MAP>(total, tiles, a.W, super, k, tile)) return;
+    if (!decode_item<MAP>(total, tiles, a.W, super, k, tile, sweep_backwards(a))) return;
 
     float *__restrict__ e = a.e + (uint64_t)k * a.ld;
     float *__restrict__ m = HAS_MU ? a.m + (uint64_t)k * a.ld : nullptr;
@@ -642,6 +650,7 @@ __global__ void def_draw_kernel(DefCtl *ctl, uint64_t d)
         start = c0 % d;
     }
     ctl->s = start;
+    ctl->backwards = (uint32_t)(ctl->t & 1u);
     ctl->t = ctl->t + 1;
     ctl->forced = -1;
 }
@@ -684,7 +693,7 @@ void def_describe_stream_kernel(const DefStepArgs &a, char *out, size_t cap)
     if (reads_x) std::snprintf(order, sizeof order, "blocked:%u", DEF_SUPER_TILES);
     else std::snprintf(order, sizeof order, "linear");
     std::snprintf(out, cap,
-                  "def_stream_vec4_kernel<mu=%d,wd=%d,detach=%d,tables=%d,threads=%u,quads=%u,nt=%d,order=%s,lds=%u>",
+                  "def_stream_vec4_kernel<mu=%d,wd=%d,detach=%d,tables=%d,threads=%u,quads=%u,nt=%d,order=%s,sweep=alternating,lds=%u>",
                   mu, wd, dt, tables, DEF_VEC_THREADS, DEF_VEC_QUADS, (int)streams_non_temporal(a), order,
                   def_stream_lds_reserve(mu, dt, streams_non_temporal(a)));
 }

@@ -12,13 +12,17 @@ from oracle.philox import block_start as oracle_block_start
 from paper_2004_05298_amd import binding
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-HEADER = os.path.join(ROOT, "include", "def.h")
+HEADERS = [os.path.join(ROOT, "include", name) for name in sorted(os.listdir(os.path.join(ROOT, "include")))
+           if name.endswith(".h")]
 
 
 def declared_functions():
-    text = open(HEADER).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(def_[a-z_]+)\s*\(", text)))
+    names = set()
+    for header in HEADERS:
+        text = open(header).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names.update(re.findall(r"\b(def_[a-z_]+)\s*\(", text))
+    return sorted(names)
 
 
 @pytest.fixture(scope="module")
@@ -156,3 +160,16 @@ def test_static_entry_point_checks_sizes_before_touching_the_gpu(lib):
                  (4096, 128, 100, 2, 0.3, 8196, None),         # output not 8-byte aligned
                  (4096, 128, 100, 2, 1.5, 8192, None)]:        # lambda outside [0, 1]
         assert call(*args) == binding.DEF_EINVAL, args
+
+
+def test_probe_rejects_bad_arguments_before_launching(lib):
+    call = lib.def_probe_stream
+    assert call(7, 4096, 8192, 1024, 1.0, 64, 1, 10240, None) == binding.DEF_EINVAL      # unknown kind
+    assert call(2, 4096, 8192, 1000, 1.0, 64, 1, 10240, None) == binding.DEF_EINVAL      # n not a multiple of 256
+    assert call(2, 4096, 8192, 0, 1.0, 64, 1, 10240, None) == binding.DEF_EINVAL
+    assert call(2, None, 8192, 1024, 1.0, 64, 1, 10240, None) == binding.DEF_EINVAL      # copy without a source
+    assert call(1, None, None, 1024, 1.0, 64, 1, 10240, None) == binding.DEF_EINVAL      # write without a destination
+    assert call(2, 4100, 8192, 1024, 1.0, 64, 1, 10240, None) == binding.DEF_EINVAL      # misaligned
+    assert call(2, 4096, 8192, 1024, 1.0, 64, 1, 70000, None) == binding.DEF_EINVAL      # LDS reservation too large
+    assert call(2, 4096, 8192, 1024, 1.0, 128, 1, 0, None) == binding.DEF_EINVAL         # shape not offered
+    assert call(2, 4096, 8192, 1024, 1.0, 64, 3, 0, None) == binding.DEF_EINVAL
