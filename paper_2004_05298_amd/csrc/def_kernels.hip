@@ -488,24 +488,28 @@ __global__ __launch_bounds__(DEF_THREADS) void def_diag_partial_kernel(DefStepAr
     double s1 = 0.0, s2 = 0.0;
     if (i < a.d) {
         double acc[4] = {0.0, 0.0, 0.0, 0.0};
-        const bool whole = i + 4 <= a.d;     // the last group of a row may be cut by d
+        if (i + 4 <= a.d) {
 #pragma unroll 16
-        for (uint32_t k = 0; k < a.W; ++k) {
-            const float *row = a.e + (uint64_t)k * a.ld + i;
-            v4f ev = (v4f)(0.0f);
-            if (whole) {
-                ev = load4<true>(row);
-            } else {
+            for (uint32_t k = 0; k < a.W; ++k) {
+                const v4f ev = load4<true>(a.e + (uint64_t)k * a.ld + i);
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    const double v = (double)ev[c];
+                    acc[c] += v;
+                    s2 += v * v;
+                }
+            }
+        } else {
+            // the last group of a row, cut by d: element by element, so that rows without
+            // zero padding (a caller's own buffers) are read only up to column d-1
+            for (uint32_t k = 0; k < a.W; ++k)
 #pragma unroll
                 for (int c = 0; c < 4; ++c)
-                    if (i + c < a.d) ev[c] = row[c];
-            }
-#pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                const double v = (double)ev[c];
-                acc[c] += v;
-                s2 += v * v;
-            }
+                    if (i + c < a.d) {
+                        const double v = (double)a.e[(uint64_t)k * a.ld + i + c];
+                        acc[c] += v;
+                        s2 += v * v;
+                    }
         }
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
@@ -613,10 +617,14 @@ __global__ __launch_bounds__(DEF_THREADS) void def_diag_workers_partial_kernel(D
 __global__ __launch_bounds__(DEF_THREADS) void def_diag_workers_final_kernel(const double *partials, uint32_t rows,
                                                                              uint32_t W, double *out)
 {
-    for (uint32_t q = threadIdx.x; q < 2 * W; q += DEF_THREADS) {
+    __shared__ double lds[DEF_THREADS / 64];
+    // one of the 2*W columns of partials at a time: every thread adds the rows r = t, t + 256, ...
+    // in order, then the workgroup adds its threads' sums (a fixed tree: reproducible)
+    for (uint32_t q = 0; q < 2 * W; ++q) {
         double sum = 0.0;
-        for (uint32_t r = 0; r < rows; ++r) sum += partials[(uint64_t)r * 2 * W + q];
-        out[q] = sum;                                       // out[k] = ||e_k||^2, out[W+k] = <e_t, e_k>
+        for (uint32_t r = threadIdx.x; r < rows; r += DEF_THREADS) sum += partials[(uint64_t)r * 2 * W + q];
+        const double total = block_sum(sum, lds);
+        if (threadIdx.x == 0) out[q] = total;               // out[k] = ||e_k||^2, out[W+k] = <e_t, e_k>
     }
     __syncthreads();
     for (uint32_t k = threadIdx.x; k < W; k += DEF_THREADS) {
