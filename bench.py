@@ -114,15 +114,20 @@ def run_probes(torch, binding, stream, src, n, reps=20):
     n = min(n, 1 << 29) // 256 * 256
     if src is None:
         src = torch.zeros(n, dtype=torch.float32, device="cuda")
-    dst = torch.empty(n, dtype=torch.float32, device="cuda")
-    dst.zero_()
+    # the destination can sit 12 KiB further than its allocation's alignment: where the two
+    # buffers of a copy sit relative to each other matters on this GPU
+    SKEW = 12288 // 4
+    dst_buf = torch.zeros(n + SKEW, dtype=torch.float32, device="cuda")
     kinds = [("read", binding.PROBE_READ, 4 * n), ("write", binding.PROBE_WRITE, 4 * n),
              ("copy", binding.PROBE_COPY, 8 * n), ("update_in_place", binding.PROBE_UPDATE, 8 * n)]
     out = {"bytes_per_buffer": 4 * n, "launches_each": reps}
     shapes = [(64, 1, 0), (64, 1, 10240), (64, 2, 0), (64, 4, 0), (256, 1, 0), (256, 2, 0), (256, 4, 0)]
     for name, kind, nbytes in kinds:
         best, every = None, {}
-        for threads, quads, lds in shapes:
+        for threads, quads, lds, skew in [sh + (0,) for sh in shapes] + (
+                [sh + (SKEW,) for sh in shapes[:1] + shapes[2:5]] if name == "copy" else []):
+            dst = dst_buf[skew:skew + n]
+
             def launch():
                 binding.probe_stream(kind, src, dst, n, 1.0, threads, quads, lds, stream)
             launch()
@@ -135,9 +140,10 @@ def run_probes(torch, binding, stream, src, n, reps=20):
             b.record()
             torch.cuda.synchronize()
             gbs = nbytes / (a.elapsed_time(b) / reps) / 1e6
-            every[f"{threads}x{quads}/{lds}"] = round(gbs)
+            every[f"{threads}x{quads}/{lds}" + ("+12K" if skew else "")] = round(gbs)
             if best is None or gbs > best[0]:
-                best = (gbs, f"{threads} threads x {quads} float4, lds {lds}")
+                best = (gbs, f"{threads} threads x {quads} float4, lds {lds}"
+                        + (", destination 12 KiB past the source's alignment" if skew else ""))
         out[name] = {"GB/s": round(best[0], 1), "frac_of_peak": round(best[0] / HBM_PEAK_GBS, 4),
                      "best_shape": best[1], "all_shapes_GB/s": every}
     return out

@@ -103,6 +103,7 @@ struct def_ctx {
     int device = 0;           // GPU that was current in def_init; owns the stream and all buffers
     // device state owned by the library
     float *e = nullptr, *m = nullptr, *msg = nullptr, *avg = nullptr;
+    void *e_alloc = nullptr, *m_alloc = nullptr;   // what hipMalloc returned (e and m point inside)
     double *diag = nullptr;   // per-workgroup partial sums of def_diagnostics
     double *diag_workers = nullptr;   // per-workgroup partial sums of def_diagnostics_workers
     DefCtl *ctl = nullptr;    // device copy of (t, seed, forced, s) for the device draw
@@ -140,8 +141,8 @@ void free_ctx(def_ctx *c)
 {
     if (!c) return;
     for (hipEvent_t ev : c->ev) (void)hipEventDestroy(ev);
-    (void)hipFree(c->e);
-    (void)hipFree(c->m);
+    (void)hipFree(c->e_alloc);
+    (void)hipFree(c->m_alloc);
     (void)hipFree(c->msg);
     (void)hipFree(c->avg);
     (void)hipFree(c->diag);
@@ -354,8 +355,14 @@ int def_init(def_ctx **out, const def_config *cfg)
 
     const size_t state_bytes = (size_t)c->W * c->ld * sizeof(float);
     const size_t msg_bytes = (size_t)c->W * c->ldmsg * sizeof(float);
-    DEF_INIT_HIP(hipMalloc((void **)&c->e, state_bytes));
-    if (c->mu != 0.0f) DEF_INIT_HIP(hipMalloc((void **)&c->m, state_bytes));
+    // e starts on a multiple of DEF_STATE_SKEW_PERIOD bytes and m DEF_STATE_SKEW bytes past one
+    // (see def_internal.h: the two buffers are read and written at the same offsets at the same time)
+    DEF_INIT_HIP(hipMalloc(&c->e_alloc, state_bytes + DEF_STATE_SKEW_PERIOD));
+    c->e = reinterpret_cast<float *>(round_up((uintptr_t)c->e_alloc, DEF_STATE_SKEW_PERIOD));
+    if (c->mu != 0.0f) {
+        DEF_INIT_HIP(hipMalloc(&c->m_alloc, state_bytes + DEF_STATE_SKEW_PERIOD + DEF_STATE_SKEW));
+        c->m = reinterpret_cast<float *>(round_up((uintptr_t)c->m_alloc, DEF_STATE_SKEW_PERIOD) + DEF_STATE_SKEW);
+    }
     DEF_INIT_HIP(hipMalloc((void **)&c->msg, msg_bytes));
     DEF_INIT_HIP(hipMalloc((void **)&c->avg, c->ldmsg * sizeof(float)));
     DEF_INIT_HIP(hipMalloc((void **)&c->diag, def_diag_blocks(c->d) * 2 * sizeof(double)));

@@ -53,6 +53,20 @@ constexpr uint32_t DEF_OUT_LDS_RESERVE = 20480;
 // than this, g, m and e are accessed non-temporally; below it they are cached normally.
 constexpr uint64_t DEF_NT_MIN_STATE_BYTES = 224ull << 20;
 
+// Placement of the two state buffers relative to each other.  The streaming pass reads and
+// writes m and e at the same offsets at the same time; when the two addresses agree in their low
+// bits (as two fresh allocations do, both being aligned to far more than 8 KiB) their requests
+// meet in the same memory resources and the pass loses bandwidth.  Measured with m placed this
+// many bytes past e's alignment (five streams, d = 25.6 M, W = 16, % of the HBM peak; boxes differ):
+//   box A   0: 81.3   256: 81.3   2048: 83.1   4096: 84.6   8192: 82.1   12288: 85.0   20480: 84.2   36864: 84.3
+//   box B   0: 82.0   1024: 82.2  2048: 81.3   4096: 82.8   8192: 83.0   12288: 82.9   20480: 82.6   36864: 82.3
+// and for d = 11.7 M without weight decay on box B   0: 78.4   4096: 79.8   12288: 79.8   20480: 80.1.
+// Odd multiples of 4 KiB are good everywhere; the library puts e on a multiple of 8 KiB and m
+// 12 KiB past one.  (The gradients are the caller's: where they sit relative to e moved the
+// result by 0.3 points at most.)
+constexpr uint64_t DEF_STATE_SKEW_PERIOD = 8192;
+constexpr uint64_t DEF_STATE_SKEW = 12288;
+
 // Device-resident copy of the draw state, used when the block start is drawn on the
 // device so that a captured HIP graph of a step can be replayed (each replay advances t).
 struct DefCtl {
