@@ -102,7 +102,8 @@ int def_destroy(def_ctx *ctx);
  *          grads + k*ld; ld >= d elements.  Tensor l sits at +off[l].  Must stay
  *          valid until the stream has executed the step.  Any 4-byte alignment
  *          and any ld >= d are accepted; 16-byte aligned rows (ld a multiple of 4)
- *          are fastest.
+ *          are fast, rows that start on 1 KiB boundaries (grads 1 KiB-aligned and ld
+ *          a multiple of 256) are fastest.
  *   y_out  DEVICE or NULL.  If not NULL, d floats receive DEF's output
  *          y_{t+1} = x_{t+1} - (1/W) sum_k e_{k,t+1}   (Algorithm 1 "Output";
  *          Sec. 3.2, Eq. (8)).  The paper needs y only when the model is
@@ -314,7 +315,7 @@ int def_block_start(uint64_t seed, uint64_t t, uint64_t d, uint64_t *start);
 /*
  * DEVICE views of the library-owned state, for checkpoints and parity checks.
  *   *e, *m       [W][*ld_state] floats, worker k's row at + k * *ld_state, column i
- *                = flat parameter index i; *ld_state >= d (a multiple of 64);
+ *                = flat parameter index i; *ld_state >= d (a multiple of 256);
  *                columns d..ld_state-1 are padding and stay zero.
  *                *m is NULL when momentum == 0.
  *   *avg_block   B floats: the averaged block C(p_t) of the last step in compact

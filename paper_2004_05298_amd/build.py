@@ -27,7 +27,8 @@ HIPCC_FLAGS = [
 
 
 def library_path() -> str:
-    return _LIB
+    """The in-tree library, or the build named by DEF_HIP_LIBRARY (to compare two builds)."""
+    return os.environ.get("DEF_HIP_LIBRARY") or _LIB
 
 
 def is_built() -> bool:

@@ -344,7 +344,7 @@ int def_init(def_ctx **out, const def_config *cfg)
         if (err != hipSuccess) { delete c; return hip_fail(err); }
     }
     c->x_flat = cfg->params;
-    c->ld = round_up(c->d, 64);
+    c->ld = round_up(c->d, DEF_STATE_ROW_MULTIPLE);
     c->ldmsg = round_up(c->B, DEF_AVG_TILE);
 
 #define DEF_INIT_HIP(call)                                                      \

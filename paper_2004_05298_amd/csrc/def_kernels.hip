@@ -226,7 +226,7 @@ __global__ __launch_bounds__(THREADS) void def_stream_vec4_kernel(DefStepArgs a,
     } else {
         // last tile of the row (a group may be cut by d or lie beyond it) or a tile
         // that crosses a tensor boundary.  The state rows are padded to a multiple of
-        // 64, so e and m can always be read as whole groups; g and x are read
+        // the tile, so e and m can always be read as whole groups; g and x are read
         // element by element where a group is cut.
 #pragma unroll
         for (int u = 0; u < U; ++u) {

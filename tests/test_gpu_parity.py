@@ -116,7 +116,7 @@ def run_case(dev, w, *, weight_decay=None, momentum=None, T=None, flat_params=Tr
     exact = {}
     try:
         e_ptr, m_ptr, a_ptr, ld_state = ctx.state_ptrs()
-        assert ld_state >= d and ld_state % 64 == 0
+        assert ld_state >= d and ld_state % 256 == 0
         assert (m_ptr != 0) == (mu != 0)
         if detach is not None:
             ctx.set_detach(w_dev, ldw, detach)
