@@ -355,13 +355,13 @@ int def_init(def_ctx **out, const def_config *cfg)
 
     const size_t state_bytes = (size_t)c->W * c->ld * sizeof(float);
     const size_t msg_bytes = (size_t)c->W * c->ldmsg * sizeof(float);
-    // e starts on a multiple of DEF_STATE_SKEW_PERIOD bytes and m DEF_STATE_SKEW bytes past one
-    // (see def_internal.h: the two buffers are read and written at the same offsets at the same time)
-    DEF_INIT_HIP(hipMalloc(&c->e_alloc, state_bytes + DEF_STATE_SKEW_PERIOD));
-    c->e = reinterpret_cast<float *>(round_up((uintptr_t)c->e_alloc, DEF_STATE_SKEW_PERIOD));
+    // e and m start at fixed offsets past a multiple of DEF_STATE_SKEW_PERIOD bytes (see
+    // def_internal.h: where the buffers sit relative to each other decides several points of bandwidth)
+    DEF_INIT_HIP(hipMalloc(&c->e_alloc, state_bytes + DEF_STATE_SKEW_PERIOD + DEF_STATE_E_OFFSET));
+    c->e = reinterpret_cast<float *>(round_up((uintptr_t)c->e_alloc, DEF_STATE_SKEW_PERIOD) + DEF_STATE_E_OFFSET);
     if (c->mu != 0.0f) {
-        DEF_INIT_HIP(hipMalloc(&c->m_alloc, state_bytes + DEF_STATE_SKEW_PERIOD + DEF_STATE_SKEW));
-        c->m = reinterpret_cast<float *>(round_up((uintptr_t)c->m_alloc, DEF_STATE_SKEW_PERIOD) + DEF_STATE_SKEW);
+        DEF_INIT_HIP(hipMalloc(&c->m_alloc, state_bytes + DEF_STATE_SKEW_PERIOD + DEF_STATE_M_OFFSET));
+        c->m = reinterpret_cast<float *>(round_up((uintptr_t)c->m_alloc, DEF_STATE_SKEW_PERIOD) + DEF_STATE_M_OFFSET);
     }
     DEF_INIT_HIP(hipMalloc((void **)&c->msg, msg_bytes));
     DEF_INIT_HIP(hipMalloc((void **)&c->avg, c->ldmsg * sizeof(float)));

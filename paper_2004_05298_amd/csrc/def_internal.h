@@ -35,13 +35,21 @@ constexpr uint32_t DEF_SUPER_TILES = 16384;
 //   g m e -> m e w   (6 streams)  32: 75    16: 78.5  14: 79.2     12: 78.6  11: 76.8
 //   g e -> e         (3 streams)  32: 82.4  25: 82.8  21: 82.0     18: 74.2  16: 71.2
 //   g e -> e w       (4 streams)  32: 76    21: 78.3  18: 78.9     16: 78.3  14: 75.4
+// (measured with m and e at the same alignment and rows on 256-byte boundaries).  With the state
+// placed as below (rows on 1 KiB boundaries, m and e apart) the five-stream optimum moves up:
+//   g m e -> m e     d = 25.6 M, weight decay   18: 84.6  17: 84.5  16: 84.0-84.5  14: 80.9  12: 71.2
+//                    d = 11.7 M, none           18: 82.7-83.6      16: 81.7-82.5  14: 80.8
+//   g m e -> m e w   16: 81.2-82.2  14: 81.9-83.1  12: 81.3  11: 77.1
+//   g e -> e w       32: 78.4  21: 81.5-82.7  18: 81.3-82.1  16: 79.2
+// (two builds, 16 against 18 per compute unit, benchmark on one box: 84.5 -> 84.9 % at d = 25.6 M,
+// 81.8 -> 83.0 % at d = 11.7 M, 81.3 -> 82.2 % at d = 138 M).
 // Steps whose state the caches can hold (see DEF_NT_MIN_STATE_BYTES) run uncapped: at
 // 137 MB per step 32 per compute unit is 2-3 % faster than 16.
 constexpr uint32_t def_stream_lds_reserve(bool has_mu, bool has_dt, bool non_temporal)
 {
     if (!non_temporal) return 0u;
-    return has_mu ? (has_dt ? 11520u : 10240u)    // 14 / 16 workgroups per compute unit
-                  : (has_dt ? 8960u : 0u);        // 18 / as many as fit (32)
+    return has_mu ? (has_dt ? 11520u : 8960u)     // 14 / 18 workgroups per compute unit
+                  : (has_dt ? 7680u : 0u);        // 21 / as many as fit (32)
 }
 // The DEF output kernel (one wave per workgroup, every thread walks the W workers of its
 // four columns with four loads in flight): 8 workgroups per compute unit.  Measured at
@@ -53,17 +61,24 @@ constexpr uint32_t DEF_OUT_LDS_RESERVE = 20480;
 // than this, g, m and e are accessed non-temporally; below it they are cached normally.
 constexpr uint64_t DEF_NT_MIN_STATE_BYTES = 224ull << 20;
 
-// Placement of the two state buffers relative to each other.  The streaming pass reads and
-// writes m and e at the same offsets at the same time; when the two addresses agree in their low
-// bits (as two fresh allocations do, both being aligned to far more than 8 KiB) their requests
-// meet in the same memory resources and the pass loses bandwidth.  Measured with m placed this
-// many bytes past e's alignment (five streams, d = 25.6 M, W = 16, % of the HBM peak; boxes differ):
+// Placement of the two state buffers relative to each other and to the gradients.  The
+// streaming pass reads g, m and e and writes m and e at the same offsets at the same time; when
+// the addresses also agree in their low bits (as fresh allocations do, all being aligned to far
+// more than 16 KiB) their requests meet in the same memory resources and the pass loses
+// bandwidth.  Measured with m placed this many bytes past e's alignment (five streams,
+// d = 25.6 M, W = 16, % of the HBM peak; boxes differ):
 //   box A   0: 81.3   256: 81.3   2048: 83.1   4096: 84.6   8192: 82.1   12288: 85.0   20480: 84.2   36864: 84.3
 //   box B   0: 82.0   1024: 82.2  2048: 81.3   4096: 82.8   8192: 83.0   12288: 82.9   20480: 82.6   36864: 82.3
 // and for d = 11.7 M without weight decay on box B   0: 78.4   4096: 79.8   12288: 79.8   20480: 80.1.
-// Odd multiples of 4 KiB are good everywhere; the library puts e on a multiple of 8 KiB and m
-// 12 KiB past one.  (The gradients are the caller's: where they sit relative to e moved the
-// result by 0.3 points at most.)
+// Odd multiples of 4 KiB are good everywhere: m sits 12 KiB past e (mod 16 KiB).  Gradient rows
+// that differ from e in address bit 12 or 13 gave another 0.4-0.9 points (three streams: 0.6-1.2);
+// gradients are the caller's and usually sit on a large power of two, so e itself is put 8 KiB
+// past a 16 KiB boundary and m 4 KiB past one (two builds, benchmark on one box, against e on the
+// boundary: 84.5 -> 84.8 % five streams, 82.7 -> 83.4 % three streams, 81.8 -> 82.5 % six).
+constexpr uint64_t DEF_STATE_SKEW_PERIOD = 16384;
+constexpr uint64_t DEF_STATE_E_OFFSET = 8192;
+constexpr uint64_t DEF_STATE_M_OFFSET = 4096;
+
 // Row stride of e and m: a multiple of the tile (256 floats = 1 KiB), so that every wave
 // instruction of the streaming pass covers exactly one aligned KiB of each state buffer.  With
 // rows that start on other 256-byte boundaries every access straddles two aligned KiB and the pass
@@ -73,8 +88,6 @@ constexpr uint64_t DEF_NT_MIN_STATE_BYTES = 224ull << 20;
 // The stride of the caller's gradient rows matters less (0 to 0.5 points).
 constexpr uint64_t DEF_STATE_ROW_MULTIPLE = 256;
 static_assert(DEF_STATE_ROW_MULTIPLE % DEF_VEC_TILE == 0, "state rows must start on tile boundaries");
-constexpr uint64_t DEF_STATE_SKEW_PERIOD = 8192;
-constexpr uint64_t DEF_STATE_SKEW = 12288;
 
 // Device-resident copy of the draw state, used when the block start is drawn on the
 // device so that a captured HIP graph of a step can be replayed (each replay advances t).

@@ -84,7 +84,7 @@ def test_whole_buffers_against_c_oracle(dev, name):
         assert ctx.last_path_flat()
         if name != "resnet56_shaped":
             # large state: the non-temporal, residency-capped instantiation
-            assert "nt=1" in ctx.last_kernel() and "lds=10240" in ctx.last_kernel(), ctx.last_kernel()
+            assert "nt=1" in ctx.last_kernel() and "lds=8960" in ctx.last_kernel(), ctx.last_kernel()
         e, m, avg = ctx.state_tensors()
         e, m, avg = e.cpu().numpy(), m.cpu().numpy(), avg.cpu().numpy()
         xg = x.cpu().numpy()
@@ -327,7 +327,7 @@ def test_large_per_tensor_gradients_and_parameters(dev):
         torch.cuda.synchronize()
         name = ctx.last_kernel()
         assert not ctx.last_path_flat()
-        assert "tables=1" in name and "nt=1" in name and "lds=10240" in name and "wd=1" in name, name
+        assert "tables=1" in name and "nt=1" in name and "lds=8960" in name and "wd=1" in name, name
         x_flat = np.concatenate([p.cpu().numpy() for p in params])
         _compare_whole_state(ctx, w, x_flat, ora, "per-tensor")
         assert_close("per-tensor: y", y.cpu().numpy(), ora.y())
@@ -369,7 +369,7 @@ def test_large_detached_points(dev, mu):
                 assert_close(f"w t={t}", wg, ref)
                 assert bit_equal(wg, ref), f"w t={t} not bit-identical"
         name = ctx.last_kernel()
-        want_lds = "lds=11520" if mu != 0 else "lds=8960"
+        want_lds = "lds=11520" if mu != 0 else "lds=7680"
         assert "detach=1" in name and "nt=1" in name and want_lds in name and f"mu={int(mu != 0)}" in name, name
         assert torch.isnan(wbuf[:, d:]).all(), "the step wrote w past column d"
         _compare_whole_state(ctx, w, x.cpu().numpy(), ora, f"detach mu={mu}")
@@ -407,7 +407,7 @@ def test_large_pack_then_apply(dev):
             assert ctx.last_block() == (s, w.B)
         torch.cuda.synchronize()
         name = ctx.last_kernel()
-        assert "nt=1" in name and "lds=10240" in name, name
+        assert "nt=1" in name and "lds=8960" in name, name
         _compare_whole_state(ctx, w, x.cpu().numpy(), ora, "pack+apply")
         assert_close("pack+apply: y", y.cpu().numpy(), ora.y())
     finally:
