@@ -412,3 +412,42 @@ def test_large_pack_then_apply(dev):
         assert_close("pack+apply: y", y.cpu().numpy(), ora.y())
     finally:
         ctx.destroy()
+
+
+@pytest.mark.timeout(600)
+def test_large_unaligned_gradient_rows(dev):
+    """Gradient rows that are only 4-byte aligned (buffer offset by one float, odd row stride)
+    at a size that selects the non-temporal instantiation: g is then read with dword-aligned
+    dwordx4 loads while the library's own rows stay on 1 KiB boundaries."""
+    w = _large()
+    d, W = w.d, w.W
+    ld = d + 3
+    print(f"[fullsize] unaligned rows: d={d} W={W} ld={ld}", flush=True)
+    x0 = wl.initial_params(w)
+    host_pool = wl.gradient_pool(w, ld=d, threads=16)
+    dev_pool = []
+    for g in host_pool:
+        buf = torch.zeros(W * ld + 8, dtype=torch.float32, device=dev)
+        view = buf[1:1 + W * ld].view(W, ld)
+        view[:, :d].copy_(torch.from_numpy(g))
+        assert view.data_ptr() % 16 == 4
+        dev_pool.append((buf, view))
+    x = torch.from_numpy(x0).to(dev)
+    y = torch.empty(d, dtype=torch.float32, device=dev)
+    ora = DefOracleC(x0, W, w.R, w.lr, w.momentum, w.weight_decay, w.seed)
+    ctx = _ctx(w, x)
+    try:
+        e_ptr, m_ptr, _, ld_state = ctx.state_ptrs()
+        # the library's own layout: rows on tile boundaries, e and m apart in their low address bits
+        assert ld_state % 256 == 0 and e_ptr % 16384 == 8192 and m_ptr % 16384 == 4096
+        for t in range(w.T):
+            ctx.step(dev_pool[t % w.pool][1], ld, y if t == w.T - 1 else None)
+            s = ora.step(host_pool[t % w.pool])
+            assert ctx.last_block() == (s, w.B)
+        torch.cuda.synchronize()
+        name = ctx.last_kernel()
+        assert "nt=1" in name and "tables=0" in name, name
+        _compare_whole_state(ctx, w, x.cpu().numpy(), ora, "unaligned rows")
+        assert_close("unaligned rows: y", y.cpu().numpy(), ora.y())
+    finally:
+        ctx.destroy()
