@@ -149,6 +149,13 @@ def run_probes(torch, binding, stream, src, n, reps=20):
     return out
 
 
+def skewed_rows(torch, W, ld, offset_bytes):
+    """A [W][ld] float32 device tensor that starts offset_bytes past its allocation's alignment."""
+    assert offset_bytes % 16 == 0
+    buf = torch.empty(W * ld + offset_bytes // 4, dtype=torch.float32, device="cuda")
+    return buf[offset_bytes // 4:].view(W, ld)
+
+
 def cpu_model() -> str:
     try:
         with open("/proc/cpuinfo") as f:
@@ -206,6 +213,9 @@ def main() -> int:
                     help="two-pass: the K timed steps run without per-launch events (value, ms_per_step), "
                          "then K more steps run with a HIP event pair around every streaming launch "
                          "(roofline); inline: the event pairs are recorded inside the timed steps")
+    ap.add_argument("--w-offset", type=int, default=0, metavar="BYTES",
+                    help="start the buffer of the detached points this many bytes (a multiple of 16) past "
+                         "its allocation's alignment")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="N",
                     help="first run N launches of the library's plain copy probe on a 1 GiB buffer (a "
                          "kernel of known traffic, 2^30 bytes read and 2^30 written per launch, against "
@@ -296,7 +306,7 @@ def main() -> int:
 
     w_out = None
     if args.detach is not None:
-        w_out = torch.empty((w.W, ld), dtype=torch.float32, device="cuda")
+        w_out = skewed_rows(torch, w.W, ld, args.w_offset)
         ctx.set_detach(w_out, ld, args.detach)
 
     y_out = torch.empty(w.d, dtype=torch.float32, device="cuda") if args.with_y else None
@@ -364,7 +374,7 @@ def main() -> int:
     aux = None
     if args.aux:
         y = torch.empty(w.d, dtype=torch.float32, device="cuda")
-        wbuf = w_out if w_out is not None else torch.empty((w.W, ld), dtype=torch.float32, device="cuda")
+        wbuf = w_out if w_out is not None else skewed_rows(torch, w.W, ld, args.w_offset)
         stats = torch.zeros(4, dtype=torch.float64, device="cuda")
         stats_w = torch.zeros(3 * w.W, dtype=torch.float64, device="cuda")
         state = 4 * w.W * w.d
