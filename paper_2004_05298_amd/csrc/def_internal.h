@@ -165,6 +165,6 @@ hipError_t def_static_scratch_address(double **ptr);
 // w_k = x - lambda*e_k for the current state (a.w, a.ldw, a.lam).
 hipError_t def_launch_detach(const DefStepArgs &a, hipStream_t st);
 // Per-worker statistics ||e_k||^2, <e_t, e_k> and their ratio lambda*(k,t), as 3*W doubles in out.
-// partials: def_diag_worker_blocks(d) * 2 * W doubles.
+// partials: def_diag_worker_blocks(d) * 2 * W doubles (an upper bound on what a launch uses).
 uint64_t def_diag_worker_blocks(uint64_t d);
 hipError_t def_launch_diagnostics_workers(const DefStepArgs &a, double *partials, double *out, hipStream_t st);

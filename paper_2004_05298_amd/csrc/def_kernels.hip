@@ -530,7 +530,8 @@ __global__ __launch_bounds__(DEF_THREADS) void def_diag_final_kernel(const doubl
 {
     __shared__ double lds[DEF_THREADS / 64];
     double s1 = 0.0, s2 = 0.0;
-    for (uint64_t b = threadIdx.x; b < n; b += DEF_THREADS) {
+#pragma unroll 8
+    for (uint64_t b = threadIdx.x; b < n; b += DEF_THREADS) {   // several loads in flight, sums in order
         s1 += partials[2 * b];
         s2 += partials[2 * b + 1];
     }
@@ -553,43 +554,77 @@ __global__ __launch_bounds__(DEF_THREADS) void def_diag_final_kernel(const doubl
 // One launch covers DIAG_KC workers k0..k0+DIAG_KC-1: a thread walks all W workers of
 // its four columns in order to form e_t there (keeping the values of the launch's own
 // workers in registers), then adds the products to 2*DIAG_KC running sums; it strides
-// over the columns with the whole grid.  The workgroup adds its threads' sums and writes
-// one row of partials; a second kernel adds the rows in a fixed order.  No atomics.
+// over the columns with the whole grid.  The grid is as many one-wave workgroups as the
+// GPU holds at once (the 2*DIAG_KC float64 sums and the DIAG_KC kept groups leave room
+// for three waves per SIMD), so all of them run from the first column to the last and
+// none waits for a second round.  Each wave adds its lanes' sums and writes one row of
+// partials; a second kernel adds the rows in a fixed order, one workgroup per worker.
+// No atomics.
 // ---------------------------------------------------------------------------
 constexpr int DIAG_KC = 16;
-constexpr uint32_t DIAG_WORKER_BLOCKS = 1024;
+constexpr uint32_t DIAG_WORKER_THREADS = 64;
+constexpr uint32_t DIAG_WORKER_ROWS_MAX = 8192;    // rows of partials the context allocates at most
+constexpr uint32_t DIAG_WORKER_ROWS_DEFAULT = 2048; // used when the occupancy query fails
 
-__global__ __launch_bounds__(DEF_THREADS) void def_diag_workers_partial_kernel(DefStepArgs a, uint32_t k0,
-                                                                               double *partials)
+__device__ __forceinline__ double wave_sum(double v)
 {
-    __shared__ double lds[DEF_THREADS / 64];
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off, 64);
+    return v;                              // valid in lane 0
+}
+
+// Adds rows k_from..k_to-1 at column group i to acc, in order; eight loads are issued before
+// the first sum needs its value.
+template <bool NT>
+__device__ __forceinline__ void diag_add_rows(const DefStepArgs &a, uint64_t i, uint32_t k_from, uint32_t k_to,
+                                              double (&acc)[4])
+{
+    uint32_t k = k_from;
+    for (; k + 8 <= k_to; k += 8) {
+        v4f ev[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) ev[u] = load4<NT>(a.e + (uint64_t)(k + u) * a.ld + i);
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+#pragma unroll
+            for (int c = 0; c < 4; ++c) acc[c] += (double)ev[u][c];
+    }
+    for (; k < k_to; ++k) {
+        const v4f ev = load4<NT>(a.e + (uint64_t)k * a.ld + i);          // padding columns hold zeros
+#pragma unroll
+        for (int c = 0; c < 4; ++c) acc[c] += (double)ev[c];
+    }
+}
+
+// FULL: the launch's DIAG_KC workers all exist (k0 + DIAG_KC <= W), so their loads carry no
+// condition and all go out before the first is used.  NT: non-temporal loads, for error
+// memories too large to stay in the caches anyway (5.73 -> 5.12 ms at d = 138 M, W = 32).
+template <bool FULL, bool NT>
+__global__ __launch_bounds__(DIAG_WORKER_THREADS) void def_diag_workers_partial_kernel(DefStepArgs a, uint32_t k0,
+                                                                                       double *partials)
+{
     double nrm[DIAG_KC], inn[DIAG_KC];
 #pragma unroll
     for (int q = 0; q < DIAG_KC; ++q) nrm[q] = inn[q] = 0.0;
-    const uint32_t k_end = min(a.W, k0 + (uint32_t)DIAG_KC);
-    const uint64_t stride = (uint64_t)gridDim.x * DEF_THREADS * 4;
-    for (uint64_t i = ((uint64_t)blockIdx.x * DEF_THREADS + threadIdx.x) * 4; i < a.d; i += stride) {
+    const uint32_t k_end = FULL ? k0 + (uint32_t)DIAG_KC : min(a.W, k0 + (uint32_t)DIAG_KC);
+    const uint64_t stride = (uint64_t)gridDim.x * DIAG_WORKER_THREADS * 4;
+    for (uint64_t i = ((uint64_t)blockIdx.x * DIAG_WORKER_THREADS + threadIdx.x) * 4; i < a.d; i += stride) {
         double acc[4] = {0.0, 0.0, 0.0, 0.0};
         v4f own[DIAG_KC];
-        for (uint32_t k = 0; k < k0; ++k) {
-            const v4f ev = load4<false>(a.e + (uint64_t)k * a.ld + i);      // padding columns hold zeros
-#pragma unroll
-            for (int c = 0; c < 4; ++c) acc[c] += (double)ev[c];
-        }
 #pragma unroll
         for (int q = 0; q < DIAG_KC; ++q) {
-            own[q] = (v4f)(0.0f);
-            if (k0 + q < k_end) {
-                own[q] = load4<false>(a.e + (uint64_t)(k0 + q) * a.ld + i);
-#pragma unroll
-                for (int c = 0; c < 4; ++c) acc[c] += (double)own[q][c];
-            }
+            // a worker past the last one reads the last one's row again and is zeroed below
+            const uint32_t k = FULL ? k0 + q : min(k0 + (uint32_t)q, k_end - 1);
+            own[q] = load4<NT>(a.e + (uint64_t)k * a.ld + i);            // padding columns hold zeros
         }
-        for (uint32_t k = k_end; k < a.W; ++k) {
-            const v4f ev = load4<false>(a.e + (uint64_t)k * a.ld + i);
+        diag_add_rows<NT>(a, i, 0, k0, acc);
 #pragma unroll
-            for (int c = 0; c < 4; ++c) acc[c] += (double)ev[c];
+        for (int q = 0; q < DIAG_KC; ++q) {
+            if (!FULL && k0 + q >= k_end) own[q] = (v4f)(0.0f);
+#pragma unroll
+            for (int c = 0; c < 4; ++c) acc[c] += (double)own[q][c];        // adding +0 changes nothing
         }
+        diag_add_rows<NT>(a, i, k_end, a.W, acc);
         double mean[4];
 #pragma unroll
         for (int c = 0; c < 4; ++c) mean[c] = acc[c] / (double)a.W;         // e_t
@@ -605,8 +640,8 @@ __global__ __launch_bounds__(DEF_THREADS) void def_diag_workers_partial_kernel(D
     double *row = partials + (uint64_t)blockIdx.x * 2 * a.W;
 #pragma unroll
     for (int q = 0; q < DIAG_KC; ++q) {
-        const double bn = block_sum(nrm[q], lds);
-        const double bi = block_sum(inn[q], lds);
+        const double bn = wave_sum(nrm[q]);
+        const double bi = wave_sum(inn[q]);
         if (threadIdx.x == 0 && k0 + q < k_end) {
             row[k0 + q] = bn;
             row[a.W + k0 + q] = bi;
@@ -614,22 +649,24 @@ __global__ __launch_bounds__(DEF_THREADS) void def_diag_workers_partial_kernel(D
     }
 }
 
+// Workgroup k adds worker k's two columns of the partials: every thread adds the rows
+// r = t, t + 256, ... in order, then the workgroup adds its threads' sums (a fixed tree).
 __global__ __launch_bounds__(DEF_THREADS) void def_diag_workers_final_kernel(const double *partials, uint32_t rows,
                                                                              uint32_t W, double *out)
 {
     __shared__ double lds[DEF_THREADS / 64];
-    // one of the 2*W columns of partials at a time: every thread adds the rows r = t, t + 256, ...
-    // in order, then the workgroup adds its threads' sums (a fixed tree: reproducible)
-    for (uint32_t q = 0; q < 2 * W; ++q) {
-        double sum = 0.0;
-        for (uint32_t r = threadIdx.x; r < rows; r += DEF_THREADS) sum += partials[(uint64_t)r * 2 * W + q];
-        const double total = block_sum(sum, lds);
-        if (threadIdx.x == 0) out[q] = total;               // out[k] = ||e_k||^2, out[W+k] = <e_t, e_k>
+    const uint32_t k = blockIdx.x;
+    double n = 0.0, in = 0.0;
+    for (uint32_t r = threadIdx.x; r < rows; r += DEF_THREADS) {
+        n += partials[(uint64_t)r * 2 * W + k];
+        in += partials[(uint64_t)r * 2 * W + W + k];
     }
-    __syncthreads();
-    for (uint32_t k = threadIdx.x; k < W; k += DEF_THREADS) {
-        const double n = out[k], in = out[W + k];
-        out[2 * W + k] = n > 0.0 ? in / n : 0.0;            // lambda*(k,t)
+    const double norm = block_sum(n, lds);
+    const double inner = block_sum(in, lds);
+    if (threadIdx.x == 0) {
+        out[k] = norm;                                      // ||e_k||^2
+        out[W + k] = inner;                                 // <e_t, e_k>
+        out[2 * W + k] = norm > 0.0 ? inner / norm : 0.0;   // lambda*(k,t)
     }
 }
 
@@ -819,21 +856,70 @@ hipError_t def_launch_diagnostics(const DefStepArgs &a, float lambda, double *pa
     return hipGetLastError();
 }
 
+namespace {
+constexpr int MAX_DEVICES = 64;
+std::mutex g_device_tables_mutex;
+uint32_t g_diag_worker_rows[MAX_DEVICES];    // one-wave workgroups of the per-worker pass each GPU holds at once
+
+uint64_t diag_worker_tiles(uint64_t d)
+{
+    const uint64_t per_wave = (uint64_t)DIAG_WORKER_THREADS * 4;
+    return (d + per_wave - 1) / per_wave;
+}
+
+// Grid of the per-worker pass on the current GPU: what is resident at once, looked up once per GPU.
+uint32_t diag_worker_resident_rows()
+{
+    int device = -1;
+    if (hipGetDevice(&device) != hipSuccess || device < 0 || device >= MAX_DEVICES) {
+        (void)hipGetLastError();
+        return DIAG_WORKER_ROWS_DEFAULT;
+    }
+    std::lock_guard<std::mutex> lock(g_device_tables_mutex);
+    if (!g_diag_worker_rows[device]) {
+        int units = 0, per_unit = 0;
+        uint32_t rows = DIAG_WORKER_ROWS_DEFAULT;
+        if (hipDeviceGetAttribute(&units, hipDeviceAttributeMultiprocessorCount, device) == hipSuccess &&
+            hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_unit, def_diag_workers_partial_kernel<true, true>,
+                                                         (int)DIAG_WORKER_THREADS, 0) == hipSuccess &&
+            units > 0 && per_unit > 0) {
+            const uint64_t resident = (uint64_t)units * (uint64_t)per_unit;
+            rows = (uint32_t)(resident < DIAG_WORKER_ROWS_MAX ? resident : DIAG_WORKER_ROWS_MAX);
+        } else {
+            (void)hipGetLastError();
+        }
+        g_diag_worker_rows[device] = rows;
+    }
+    return g_diag_worker_rows[device];
+}
+}  // namespace
+
 uint64_t def_diag_worker_blocks(uint64_t d)
 {
-    const uint64_t need = def_diag_blocks(d);
-    return need < DIAG_WORKER_BLOCKS ? need : DIAG_WORKER_BLOCKS;
+    const uint64_t need = diag_worker_tiles(d);
+    return need < DIAG_WORKER_ROWS_MAX ? need : DIAG_WORKER_ROWS_MAX;
 }
 
 hipError_t def_launch_diagnostics_workers(const DefStepArgs &a, double *partials, double *out, hipStream_t st)
 {
-    const uint32_t rows = (uint32_t)def_diag_worker_blocks(a.d);
+    const uint64_t need = diag_worker_tiles(a.d);
+    const uint32_t resident = diag_worker_resident_rows();
+    const uint32_t rows = (uint32_t)(need < resident ? need : resident);      // <= def_diag_worker_blocks(d)
+    const bool nt = (uint64_t)a.W * a.ld * sizeof(float) > DEF_NT_MIN_STATE_BYTES;
     for (uint32_t k0 = 0; k0 < a.W; k0 += DIAG_KC) {
-        def_diag_workers_partial_kernel<<<dim3(rows), dim3(DEF_THREADS), 0, st>>>(a, k0, partials);
+        const bool full = k0 + DIAG_KC <= a.W;
+        const dim3 grid(rows), block(DIAG_WORKER_THREADS);
+        if (nt) {
+            if (full) def_diag_workers_partial_kernel<true, true><<<grid, block, 0, st>>>(a, k0, partials);
+            else def_diag_workers_partial_kernel<false, true><<<grid, block, 0, st>>>(a, k0, partials);
+        } else {
+            if (full) def_diag_workers_partial_kernel<true, false><<<grid, block, 0, st>>>(a, k0, partials);
+            else def_diag_workers_partial_kernel<false, false><<<grid, block, 0, st>>>(a, k0, partials);
+        }
         const hipError_t err = hipGetLastError();
         if (err != hipSuccess) return err;
     }
-    def_diag_workers_final_kernel<<<dim3(1), dim3(DEF_THREADS), 0, st>>>(partials, rows, a.W, out);
+    def_diag_workers_final_kernel<<<dim3(a.W), dim3(DEF_THREADS), 0, st>>>(partials, rows, a.W, out);
     return hipGetLastError();
 }
 
@@ -847,9 +933,7 @@ hipError_t def_launch_diagnostics_workers(const DefStepArgs &a, double *partials
 static __device__ __align__(256) double def_static_scratch[DEF_STATIC_SCRATCH_DOUBLES];
 
 namespace {
-constexpr int MAX_DEVICES = 64;
 double *g_static_scratch_ptr[MAX_DEVICES];   // device address of def_static_scratch on each GPU
-std::mutex g_static_scratch_mutex;
 }  // namespace
 
 hipError_t def_static_scratch_address(double **ptr)
@@ -858,7 +942,7 @@ hipError_t def_static_scratch_address(double **ptr)
     hipError_t err = hipGetDevice(&device);
     if (err != hipSuccess) return err;
     if (device < 0 || device >= MAX_DEVICES) return hipErrorInvalidDevice;
-    std::lock_guard<std::mutex> lock(g_static_scratch_mutex);
+    std::lock_guard<std::mutex> lock(g_device_tables_mutex);
     if (!g_static_scratch_ptr[device]) {
         void *found = nullptr;
         err = hipGetSymbolAddress(&found, HIP_SYMBOL(def_static_scratch));   // for the current GPU
