@@ -374,6 +374,7 @@ int def_init(def_ctx **out, const def_config *cfg)
         // a later call of it (possibly while the stream is being captured) finds it resolved
         double *unused = nullptr;
         DEF_INIT_HIP(def_static_scratch_address(&unused));
+        def_prepare_diagnostics_workers();   // likewise: the grid of the per-worker statistics
     }
     DEF_INIT_HIP(hipMemsetAsync(c->ctl, 0, sizeof(DefCtl), c->stream));
 

@@ -167,4 +167,7 @@ hipError_t def_launch_detach(const DefStepArgs &a, hipStream_t st);
 // Per-worker statistics ||e_k||^2, <e_t, e_k> and their ratio lambda*(k,t), as 3*W doubles in out.
 // partials: def_diag_worker_blocks(d) * 2 * W doubles (an upper bound on what a launch uses).
 uint64_t def_diag_worker_blocks(uint64_t d);
+// Looks up, once per GPU, how many workgroups of the per-worker pass the current GPU holds at
+// once (its grid), so that the first def_launch_diagnostics_workers asks the runtime nothing.
+void def_prepare_diagnostics_workers();
 hipError_t def_launch_diagnostics_workers(const DefStepArgs &a, double *partials, double *out, hipStream_t st);

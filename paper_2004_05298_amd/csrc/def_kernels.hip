@@ -894,6 +894,8 @@ uint32_t diag_worker_resident_rows()
 }
 }  // namespace
 
+void def_prepare_diagnostics_workers() { (void)diag_worker_resident_rows(); }
+
 uint64_t def_diag_worker_blocks(uint64_t d)
 {
     const uint64_t need = diag_worker_tiles(d);
