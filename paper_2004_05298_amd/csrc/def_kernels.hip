@@ -611,19 +611,19 @@ __global__ __launch_bounds__(DIAG_WORKER_THREADS) void def_diag_workers_partial_
     for (uint64_t i = ((uint64_t)blockIdx.x * DIAG_WORKER_THREADS + threadIdx.x) * 4; i < a.d; i += stride) {
         double acc[4] = {0.0, 0.0, 0.0, 0.0};
         v4f own[DIAG_KC];
+        // all loads first, none of them used before the last is issued; a worker past the
+        // last one (uniform over the wave) is not loaded and counts as zeros
 #pragma unroll
         for (int q = 0; q < DIAG_KC; ++q) {
-            // a worker past the last one reads the last one's row again and is zeroed below
-            const uint32_t k = FULL ? k0 + q : min(k0 + (uint32_t)q, k_end - 1);
-            own[q] = load4<NT>(a.e + (uint64_t)k * a.ld + i);            // padding columns hold zeros
+            own[q] = (v4f)(0.0f);
+            if (FULL || k0 + q < k_end)
+                own[q] = load4<NT>(a.e + (uint64_t)(k0 + q) * a.ld + i);   // padding columns hold zeros
         }
         diag_add_rows<NT>(a, i, 0, k0, acc);
 #pragma unroll
-        for (int q = 0; q < DIAG_KC; ++q) {
-            if (!FULL && k0 + q >= k_end) own[q] = (v4f)(0.0f);
+        for (int q = 0; q < DIAG_KC; ++q)
 #pragma unroll
             for (int c = 0; c < 4; ++c) acc[c] += (double)own[q][c];        // adding +0 changes nothing
-        }
         diag_add_rows<NT>(a, i, k_end, a.W, acc);
         double mean[4];
 #pragma unroll
