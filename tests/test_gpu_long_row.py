@@ -44,6 +44,7 @@ def test_row_longer_than_2_32_columns():
         pytest.skip("no GPU")
     torch.cuda.set_device(0)
     dev = torch.device("cuda:0")
+    torch.cuda.empty_cache()              # what earlier tests left in torch's cache counts as used
     free, _ = torch.cuda.mem_get_info()
     if free < NEED_BYTES:
         pytest.skip(f"needs {NEED_BYTES >> 30} GiB of free device memory, {free >> 30} GiB free")
@@ -132,3 +133,5 @@ def test_row_longer_than_2_32_columns():
         assert bit_equal(eg, ora.e) and bit_equal(mg, ora.m)
     finally:
         ctx.destroy()
+        del x, y, pool
+        torch.cuda.empty_cache()
