@@ -176,3 +176,67 @@ def test_captured_pointer_table_survives_other_tables(dev):
             assert ctx.get_step() == t
     finally:
         ctx.destroy()
+
+
+def test_captured_iteration_with_detached_points_and_statistics(dev):
+    """Everything a training iteration may enqueue besides the step is captured with it: the
+    step writes the detached points, then come def_output, the stand-alone def_detach with
+    another lambda, both sets of error-memory statistics and the statistics entry point that
+    allocates nothing.  A call that allocated, copied or synchronised would break the capture;
+    each replay's outputs are compared with the oracle."""
+    from paper_2004_05298_amd import binding
+    stream = torch.cuda.Stream()
+    w, ld, pool, gdev, x, ora, ctx = _setup(dev, stream, d=41003, W=19, R=7, T=12, wd=1e-4, L=5)
+    W, d = w.W, w.d
+    lam = float(np.float32(0.3))
+    lam2 = float(np.float32(0.75))
+    try:
+        with torch.cuda.stream(stream):
+            static = torch.zeros_like(gdev[0])
+            y = torch.zeros(d, dtype=torch.float32, device=dev)
+            pts = torch.zeros((W, ld), dtype=torch.float32, device=dev)
+            pts2 = torch.zeros((W, ld), dtype=torch.float32, device=dev)
+            diag = torch.zeros(4, dtype=torch.float64, device=dev)
+            diag_static = torch.zeros(4, dtype=torch.float64, device=dev)
+            per_worker = torch.zeros(3 * W, dtype=torch.float64, device=dev)
+        ctx.set_device_draw(True)
+        ctx.set_detach(pts, ld, lam)
+        ctx.step(gdev[0], ld)                       # one eager step (also warms the kernels up)
+        ora.step(pool[0][:, :d])
+        e, _, _ = ctx.state_tensors()
+        ld_state = e.stride(0)
+        stream.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=stream):
+            ctx.step(static, ld)
+            ctx.output(y)
+            ctx.detach(pts2, ld, lam2)
+            ctx.diagnostics(lam, diag)
+            ctx.diagnostics_workers(per_worker)
+            binding.diagnostics_static(e.data_ptr(), ld_state, d, W, lam, diag_static, stream.cuda_stream)
+        stream.synchronize()
+        _check_state(ctx, x, ora, d, "capture must not execute anything")
+        t = 1
+        for replay in range(4):
+            with torch.cuda.stream(stream):
+                static.copy_(gdev[t % w.pool])       # eager work between replays
+                graph.replay()
+            stream.synchronize()
+            ora.step(pool[t % w.pool][:, :d])
+            t += 1
+            where = f"replay {replay}"
+            _check_state(ctx, x, ora, d, where)
+            assert bit_equal(y.cpu().numpy(), ora.y()), f"{where}: y"
+            assert bit_equal(pts.cpu().numpy()[:, :d], ora.detached_points(lam)), f"{where}: w of the step"
+            assert bit_equal(pts2.cpu().numpy()[:, :d], ora.detached_points(lam2)), f"{where}: def_detach"
+            got, ref = diag.cpu().numpy(), ora.diagnostics(lam)
+            scale = ref["mean_sq"]
+            assert abs(got[0] - ref["bar_sq"]) <= 1e-10 * scale and abs(got[1] - ref["mean_sq"]) <= 1e-10 * scale
+            assert abs(got[2] - ref["lam_star"]) <= 1e-9 and abs(got[3] - ref["dist"]) <= 1e-9 * scale
+            assert np.array_equal(diag_static.cpu().numpy(), got), f"{where}: static statistics differ"
+            pw, refw = per_worker.cpu().numpy(), ora.diagnostics_workers()
+            assert np.abs(pw[:W] - refw["norm_sq"]).max() <= 1e-10 * scale * W
+            assert np.abs(pw[W:2 * W] - refw["inner"]).max() <= 1e-10 * scale * W
+            assert np.abs(pw[2 * W:] - refw["lam_star"]).max() <= 1e-9
+    finally:
+        ctx.destroy()
