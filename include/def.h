@@ -62,7 +62,7 @@ typedef struct def_ctx def_ctx; /* opaque, owned by the library */
  */
 typedef struct def_config {
     uint64_t d;             /* number of parameters, 1 <= d < 2^40                              */
-    uint32_t W;             /* number of workers (the paper's K), >= 1; W * ceil(d/256) must be
+    uint32_t W;             /* number of workers (the paper's K), >= 1; W * (ceil(d/256) + 7) must be
                                below 2^31 (one workgroup per worker and 256 indices)            */
     uint32_t R;             /* compression ratio, integer, 1 <= R <= d.  The kept block has
                                B = ceil(d/R) elements (delta = B/d, Assumption 4.2).            */

@@ -326,10 +326,10 @@ int def_init(def_ctx **out, const def_config *cfg)
     }
 
     {
-        // one workgroup per (worker, tile): the grid must fit 31 bits
+        // one workgroup per (worker, tile), up to 7 idle ones per worker: the grid must fit 31 bits
         const uint64_t grid_limit = 0x7fffffffull - 8;
         const uint64_t vec_tiles = (cfg->d + DEF_VEC_TILE - 1) / DEF_VEC_TILE;
-        if (vec_tiles * cfg->W > grid_limit) return DEF_EINVAL;
+        if ((vec_tiles + 7) * cfg->W > grid_limit) return DEF_EINVAL;
     }
 
     def_ctx *c = new (std::nothrow) def_ctx;

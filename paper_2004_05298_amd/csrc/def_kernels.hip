@@ -131,8 +131,14 @@ __device__ __forceinline__ bool decode_item(uint64_t total, uint64_t tiles, uint
         const uint64_t rem = item - sup * per_super;
         const uint64_t first = sup * super;                   // first tile of this super-tile
         const uint64_t width = tiles - first < super ? tiles - first : super;   // last one may be short
-        k = (uint32_t)(rem / width);
-        tile = first + (rem - (uint64_t)k * width);
+        // every worker's piece takes a multiple of 8 items (the last few of a short piece do
+        // nothing), so that a tile falls to the same XCD for all W workers and the x it reads
+        // is found in that XCD's L2; `super` is a multiple of 8 itself
+        const uint64_t slots = (width + 7) & ~(uint64_t)7;
+        k = (uint32_t)(rem / slots);
+        const uint64_t within = rem - (uint64_t)k * slots;
+        if (within >= width) return false;
+        tile = first + within;
     }
     return true;
 }
@@ -713,6 +719,15 @@ uint32_t grid_for(uint64_t total)
     return (uint32_t)((total + 7) / 8 * 8);                   // whole rounds over the 8 XCDs
 }
 
+// Work items of the blocked order: per worker, the full super-tiles and the last, short one
+// rounded up to a multiple of 8 tiles (see decode_item).
+uint64_t blocked_items(uint64_t tiles, uint32_t W)
+{
+    static_assert(DEF_SUPER_TILES % 8 == 0, "a super-tile must be whole rounds over the 8 XCDs");
+    const uint64_t full = tiles / DEF_SUPER_TILES, last = tiles % DEF_SUPER_TILES;
+    return (full * DEF_SUPER_TILES + (last + 7) / 8 * 8) * W;
+}
+
 }  // namespace
 
 // g, m and e are touched once per step.  What can stay in the 256 MiB Infinity Cache
@@ -787,7 +802,8 @@ hipError_t def_launch_stream(const DefStepArgs &a, hipStream_t st)
 {
     const uint64_t per_tile = DEF_VEC_TILE;
     const uint64_t tiles = (a.d + per_tile - 1) / per_tile;
-    const uint64_t total = tiles * a.W;
+    const bool blocked = a.wd != 0.0f || a.w != nullptr;      // as DEF_DISPATCH chooses the order
+    const uint64_t total = blocked ? blocked_items(tiles, a.W) : tiles * a.W;
     if (total > 0x7fffffffull - 8) return hipErrorInvalidConfiguration;
     const dim3 grid(grid_for(total)), block(DEF_VEC_THREADS);
     const bool nt = streams_non_temporal(a);
@@ -960,7 +976,7 @@ hipError_t def_launch_detach(const DefStepArgs &a, hipStream_t st)
 {
     static_assert(DEF_VEC_QUADS == 1, "def_detach_kernel handles one group per thread");
     const uint64_t tiles = (a.d + DEF_VEC_TILE - 1) / DEF_VEC_TILE;
-    const uint64_t total = tiles * a.W;
+    const uint64_t total = blocked_items(tiles, a.W);
     if (total > 0x7fffffffull - 8) return hipErrorInvalidConfiguration;
     // two loads and one store of 1 KiB per wave: as many waves as fit (32 per compute unit:
     // 79 % of the HBM peak; capped at 16: 62 %)
